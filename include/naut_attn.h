@@ -1,0 +1,97 @@
+/*
+ * naut_attn.h -- C ABI of the fused attention forward for AMD MI355X (gfx950).
+ *
+ * The operation is the one the paper's auto-scheduler exists to speed up
+ * (Section 1: attention written as "matmuls and softmax"; operator table of
+ * Section 6: Global, Causal and Grouped-Query attention): for every batch b,
+ * query head h and query position i
+ *
+ *     s_ij = scale * sum_d q[b,h,i,d] * k[b,hk,j,d]            j in J_i
+ *     P_ij = exp(s_ij - m_i) / l_i,  m_i = max_j s_ij,  l_i = sum_j exp(s_ij - m_i)
+ *     o[b,h,i,:] = sum_j P_ij * v[b,hk,j,:]
+ *     lse[b,h,i] = m_i + ln l_i                                 (natural log)
+ *
+ * with J_i = {0..S-1}, or {0..i} when `causal` is non-zero (the diagonal is
+ * kept), and hk = h / (Hq/Hkv): consecutive query heads share a key/value head.
+ * It is computed in ONE kernel: the reductions over j are fused with the
+ * rolling-update ("online") scheme of Section 4.2/4.3, so the S x S score
+ * matrix never reaches memory; the running maximum introduces the repair factor
+ * exp(m_old - m_new).  The three rewrites of the expression-rewriting table of
+ * Section 5 are applied by hand: `scale` is hoisted out of the loop into one
+ * constant, the per-step division by l is replaced by one division at the end,
+ * and exp(x) is evaluated as exp2(log2(e) * x).
+ *
+ * Memory: every pointer is DEVICE memory owned by the caller, contiguous and
+ * row-major with D innermost:
+ *     q, o : [B][Hq][S][D]      k, v : [B][Hkv][S][D]      lse : [B][Hq][S] (fp32)
+ * q/k/v/o must be 16-byte aligned, lse 4-byte aligned.  `lse` may be NULL (not
+ * written then).  The library allocates nothing, keeps no state between calls
+ * and never frees.  `stream` is a hipStream_t passed as void* (NULL = the
+ * default stream).  Calls are asynchronous: work is enqueued on `stream` and the
+ * call returns without synchronising.
+ *
+ * Errors: every argument is validated on the host before any HIP call; a
+ * negative naut_status is returned and naut_last_error_string() explains it.
+ * Nothing aborts or throws across this boundary.
+ */
+#ifndef NAUT_ATTN_H
+#define NAUT_ATTN_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NAUT_OK = 0,
+    NAUT_ERR_NULL = -1,        /* q, k, v or o is NULL */
+    NAUT_ERR_SHAPE = -2,       /* a size <= 0, Hq % Hkv != 0, or scale not finite */
+    NAUT_ERR_UNSUPPORTED = -3, /* D not in {64,128}, unknown dtype pair, scale < 0, size beyond 32-bit grid limits */
+    NAUT_ERR_ALIGN = -4,       /* q/k/v/o not 16-byte aligned or lse not 4-byte aligned */
+    NAUT_ERR_HIP = -5          /* the launch failed; see naut_last_error_string() */
+} naut_status;
+
+typedef enum {
+    NAUT_BF16 = 0,
+    NAUT_F16 = 1,
+    NAUT_F32 = 2 /* output only */
+} naut_dtype;
+
+/*
+ * Fused attention forward, bf16 q/k/v -> bf16 o (round to nearest even), fp32 lse.
+ * Arguments: device pointers as described above; B batch, Hq query heads, Hkv
+ * key/value heads (Hq % Hkv == 0), S sequence length (queries and keys), D head
+ * dimension (64 or 128); causal != 0 selects J_i = {0..i}; scale >= 0 multiplies
+ * the scores (typically 1/sqrt(D)); stream as above.  Any S >= 1 is handled
+ * (ragged tails are masked inside the kernel).
+ * Returns NAUT_OK or a negative naut_status.
+ */
+int naut_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                  int B, int Hq, int Hkv, int S, int D, int causal, float scale, void* stream);
+
+/*
+ * Same computation with explicit storage types.  in_dtype is the type of q, k
+ * and v (NAUT_BF16 or NAUT_F16); out_dtype the type of o (in_dtype, or
+ * NAUT_F32 for an unrounded fp32 output).  The matrix products run in in_dtype
+ * with fp32 accumulation; the softmax runs in fp32.
+ */
+int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float* lse,
+                     int B, int Hq, int Hkv, int S, int D, int causal, float scale, void* stream,
+                     int in_dtype, int out_dtype);
+
+/* Message for the last non-OK status returned on the calling thread ("" if none). Never NULL. */
+const char* naut_last_error_string(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int naut_version(void);
+
+/*
+ * Name of the kernel variant naut_attn_fwd_dt would launch for these arguments
+ * (a static string such as "fwd_d128_bm128_bn64_w4"), or NULL if unsupported.
+ * Host only; used by the benchmark to match profiler rows to launches.
+ */
+const char* naut_attn_variant_name(int S, int D, int causal, int in_dtype, int out_dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NAUT_ATTN_H */

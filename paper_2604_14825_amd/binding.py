@@ -1,0 +1,122 @@
+"""ctypes binding of the C-ABI library: argument marshalling only.
+
+Every step of the attention forward runs inside ``libnaut_attn.so`` (HIP,
+gfx950).  There is no CPU or PyTorch fallback: if the library has not been
+built, importing its symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnaut_attn.so")
+
+NAUT_OK = 0
+NAUT_ERR_NULL = -1
+NAUT_ERR_SHAPE = -2
+NAUT_ERR_UNSUPPORTED = -3
+NAUT_ERR_ALIGN = -4
+NAUT_ERR_HIP = -5
+
+NAUT_BF16 = 0
+NAUT_F16 = 1
+NAUT_F32 = 2
+
+EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
+           "naut_attn_variant_name")
+
+_lib = None
+
+
+class NautError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("naut_attn status %d: %s" % (code, msg))
+        self.code = code
+
+
+def lib():
+    """The loaded C-ABI library (raises if it was never built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libnaut_attn.so is missing: build it with `python -m paper_2604_14825_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        L.naut_attn_fwd.restype = ci
+        L.naut_attn_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp]
+        L.naut_attn_fwd_dt.restype = ci
+        L.naut_attn_fwd_dt.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, ci, ci]
+        L.naut_last_error_string.restype = ctypes.c_char_p
+        L.naut_last_error_string.argtypes = []
+        L.naut_version.restype = ci
+        L.naut_version.argtypes = []
+        L.naut_attn_variant_name.restype = ctypes.c_char_p
+        L.naut_attn_variant_name.argtypes = [ci, ci, ci, ci, ci]
+        _lib = L
+    return _lib
+
+
+def last_error_string() -> str:
+    return lib().naut_last_error_string().decode()
+
+
+def version() -> int:
+    return int(lib().naut_version())
+
+
+def variant_name(S: int, D: int, causal: bool, in_dtype: int, out_dtype: int):
+    r = lib().naut_attn_variant_name(S, D, int(bool(causal)), in_dtype, out_dtype)
+    return r.decode() if r is not None else None
+
+
+def naut_attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, S, D, causal, scale, stream_ptr,
+                      in_dtype=None, out_dtype=None) -> int:
+    """Direct call with integer device addresses; returns the status code."""
+    L = lib()
+    if in_dtype is None and out_dtype is None:
+        return int(L.naut_attn_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, S, D, int(causal),
+                                   float(scale), stream_ptr))
+    return int(L.naut_attn_fwd_dt(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, S, D, int(causal),
+                                  float(scale), stream_ptr, int(in_dtype), int(out_dtype)))
+
+
+def _torch_dtype_code(t):
+    import torch
+    return {torch.bfloat16: NAUT_BF16, torch.float16: NAUT_F16, torch.float32: NAUT_F32}[t.dtype]
+
+
+def naut_attn_fwd(q, k, v, o, lse, causal: bool, scale: float, stream=None):
+    """Fused attention forward on torch device tensors (used for memory and streams only).
+
+    q,o [B,Hq,S,D]; k,v [B,Hkv,S,D]; lse [B,Hq,S] fp32 or None; all contiguous, on one GPU.
+    Enqueues on `stream` (a torch.cuda.Stream; default: the current stream) and returns.
+    """
+    import torch
+    for t in (q, k, v, o):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("q, k, v, o must be contiguous device tensors")
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    if tuple(k.shape) != (B, Hkv, S, D) or tuple(v.shape) != (B, Hkv, S, D) or tuple(o.shape) != (B, Hq, S, D):
+        raise ValueError("shape mismatch between q, k, v, o")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share one dtype")
+    lse_ptr = None
+    if lse is not None:
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, Hq, S)):
+            raise ValueError("lse must be a contiguous fp32 device tensor [B,Hq,S]")
+        lse_ptr = lse.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    in_dt, out_dt = _torch_dtype_code(q), _torch_dtype_code(o)
+    if in_dt == NAUT_BF16 and out_dt == NAUT_BF16:
+        rc = naut_attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, S, D,
+                               causal, scale, stream.cuda_stream)
+    else:
+        rc = naut_attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, S, D,
+                               causal, scale, stream.cuda_stream, in_dt, out_dt)
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())

@@ -1,0 +1,76 @@
+"""C-ABI: the library loads, exports what the header declares, and validates arguments on the host
+(no compute call needs a GPU here: every check below returns before any HIP call)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_14825_amd import binding as nb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "naut_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(naut_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_exported():
+    syms = declared_symbols()
+    assert set(syms) == set(nb.EXPORTS)
+    L = ctypes.CDLL(nb.LIB_PATH)
+    for s in syms:
+        assert hasattr(L, s), s
+
+
+def test_version_and_variant_name():
+    assert nb.version() >= 100
+    assert nb.variant_name(16384, 128, True, nb.NAUT_BF16, nb.NAUT_BF16)
+    assert nb.variant_name(1024, 64, False, nb.NAUT_F16, nb.NAUT_F32)
+    assert nb.variant_name(1024, 96, False, nb.NAUT_BF16, nb.NAUT_BF16) is None
+
+
+A = 0x10000  # a fake, 16-byte aligned, never dereferenced device address
+
+
+def call(q=A, k=A, v=A, o=A, lse=A, B=1, Hq=2, Hkv=2, S=128, D=64, causal=0, scale=0.125, dt=None):
+    if dt is None:
+        return nb.naut_attn_fwd_raw(q, k, v, o, lse, B, Hq, Hkv, S, D, causal, scale, None)
+    return nb.naut_attn_fwd_raw(q, k, v, o, lse, B, Hq, Hkv, S, D, causal, scale, None, dt[0], dt[1])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(q=None), nb.NAUT_ERR_NULL),
+    (dict(k=None), nb.NAUT_ERR_NULL),
+    (dict(v=None), nb.NAUT_ERR_NULL),
+    (dict(o=None), nb.NAUT_ERR_NULL),
+    (dict(B=0), nb.NAUT_ERR_SHAPE),
+    (dict(S=0), nb.NAUT_ERR_SHAPE),
+    (dict(S=-5), nb.NAUT_ERR_SHAPE),
+    (dict(Hq=3, Hkv=2), nb.NAUT_ERR_SHAPE),
+    (dict(Hkv=0), nb.NAUT_ERR_SHAPE),
+    (dict(scale=float("nan")), nb.NAUT_ERR_SHAPE),
+    (dict(scale=float("inf")), nb.NAUT_ERR_SHAPE),
+    (dict(scale=-1.0), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(D=96), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(D=256), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(dt=(nb.NAUT_F32, nb.NAUT_F32)), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(dt=(nb.NAUT_BF16, nb.NAUT_F16)), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(dt=(7, 0)), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(q=A + 8), nb.NAUT_ERR_ALIGN),
+    (dict(o=A + 2), nb.NAUT_ERR_ALIGN),
+    (dict(lse=A + 2), nb.NAUT_ERR_ALIGN),
+])
+def test_argument_validation(kw, code):
+    assert call(**kw) == code
+    msg = nb.last_error_string()
+    assert isinstance(msg, str) and len(msg) > 0
+
+
+def test_missing_library_is_loud(monkeypatch, tmp_path):
+    monkeypatch.setattr(nb, "_lib", None)
+    monkeypatch.setattr(nb, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        nb.lib()

@@ -1,0 +1,114 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on identical seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_14825_amd import binding as nb
+from paper_2604_14825_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    # B, Hq, Hkv, S, D, causal, in, out      (several tiles, ragged tails, degenerate sizes)
+    (1, 1, 1, 1, 64, False, synth.BF16, synth.BF16),
+    (1, 1, 1, 1, 128, True, synth.BF16, synth.BF16),
+    (1, 2, 1, 7, 64, True, synth.F16, synth.F32),
+    (2, 2, 2, 63, 128, True, synth.BF16, synth.BF16),
+    (1, 2, 2, 64, 128, False, synth.BF16, synth.BF16),
+    (1, 2, 2, 65, 64, False, synth.BF16, synth.F32),
+    (2, 4, 2, 129, 128, True, synth.BF16, synth.BF16),
+    (1, 3, 1, 200, 64, True, synth.BF16, synth.BF16),
+    (1, 2, 2, 257, 128, False, synth.F16, synth.F16),
+    (2, 4, 2, 333, 64, True, synth.F16, synth.F16),
+    (1, 8, 2, 400, 128, True, synth.BF16, synth.F32),
+    (1, 2, 2, 512, 128, True, synth.BF16, synth.BF16),
+    (1, 2, 1, 777, 128, False, synth.BF16, synth.BF16),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D,causal,idt,odt", SMALL)
+def test_small_shapes_elementwise(B, Hq, Hkv, S, D, causal, idt, odt):
+    seed = 1000 + S * 7 + D
+    q = synth.fill(B, Hq, S, D, seed, synth.TAG_Q, idt)
+    k = synth.fill(B, Hkv, S, D, seed, synth.TAG_K, idt, S // 50, 8.0)
+    v = synth.fill(B, Hkv, S, D, seed, synth.TAG_V, idt)
+    scale = 1.0 / math.sqrt(D)
+    print("case", B, Hq, Hkv, S, D, causal, idt, odt, flush=True)
+    o, lse = gu.run_hip(q, k, v, idt, odt, causal, scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal, scale)
+    gu.check(o, lse, o_ref, lse_ref, "small")
+
+
+def test_tiny_workload_full():
+    w = synth.WORKLOADS["tiny"]
+    q, k, v = synth.make_inputs(w)
+    o, lse = gu.run_hip(q, k, v, w.in_dtype, w.out_dtype, w.causal, w.scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, w.in_dtype, w.causal, w.scale)
+    mx, mean = gu.check(o, lse, o_ref, lse_ref, "tiny")
+    # fp16 inputs, fp32 output: only P's rounding to fp16 and fp32 accumulation remain
+    assert mx < 5e-3
+
+
+def test_encoder_workload_full():
+    w = synth.WORKLOADS["encoder"]
+    q, k, v = synth.make_inputs(w)
+    o, lse = gu.run_hip(q, k, v, w.in_dtype, w.out_dtype, w.causal, w.scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, w.in_dtype, w.causal, w.scale)
+    gu.check(o, lse, o_ref, lse_ref, "encoder")
+
+
+@pytest.mark.parametrize("name,nrand", [("prefill", 4096), ("gqa", 3072), ("long", 3072)])
+def test_large_workloads_sampled_rows(name, nrand):
+    """Full-size launch (the configuration bench.py times); the oracle computes a declared row subset
+    (every output row depends only on its own query row, so a subset is exact)."""
+    w = synth.WORKLOADS[name]
+    print("workload", name, flush=True)
+    q, k, v = synth.make_inputs(w)
+    o, lse = gu.run_hip(q, k, v, w.in_dtype, w.out_dtype, w.causal, w.scale)
+    assert np.isfinite(o).all() and np.isfinite(lse).all()
+    rows = gu.sample_rows(w, nrand, seed=17)
+    if w.n_outlier:
+        # rows whose diagonal tile holds an outlier key, and the outlier rows themselves
+        out = synth.outlier_rows(0, w.S, synth.workload_seed(w), synth.TAG_K, w.n_outlier)
+        rows = np.unique(np.concatenate([rows, out[:64].astype(np.int64), np.minimum(out[:64].astype(np.int64) + 1, w.S - 1)]))
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, w.in_dtype, w.causal, w.scale, rows=rows)
+    gu.check(o.reshape(-1, w.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, name)
+
+
+def test_run_to_run_bit_identical():
+    w = synth.WORKLOADS["encoder"]
+    q, k, v = synth.make_inputs(w)
+    o1, l1 = gu.run_hip(q, k, v, w.in_dtype, w.out_dtype, w.causal, w.scale)
+    o2, l2 = gu.run_hip(q, k, v, w.in_dtype, w.out_dtype, w.causal, w.scale)
+    np.testing.assert_array_equal(o1, o2)
+    np.testing.assert_array_equal(l1, l2)
+
+
+def test_lse_null_and_side_stream():
+    w = synth.WORKLOADS["tiny"]
+    q, k, v = synth.make_inputs(w)
+    o_ref, _ = gu.run_hip(q, k, v, w.in_dtype, w.out_dtype, w.causal, w.scale)
+    qd, kd, vd = (gu.to_device(a, w.in_dtype) for a in (q, k, v))
+    o = torch.zeros((w.B, w.Hq, w.S, w.D), dtype=torch.float32, device="cuda")
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    nb.naut_attn_fwd(qd, kd, vd, o, None, w.causal, w.scale, stream=st)
+    st.synchronize()
+    np.testing.assert_array_equal(o.double().cpu().numpy(), o_ref)
+
+
+def test_zero_scale_and_property_checks():
+    # scale = 0: uniform attention -> prefix means of V, lse = ln(i+1)
+    B, H, S, D = 1, 2, 300, 64
+    q = synth.fill(B, H, S, D, 5, synth.TAG_Q, synth.BF16)
+    k = synth.fill(B, H, S, D, 5, synth.TAG_K, synth.BF16)
+    v = synth.fill(B, H, S, D, 5, synth.TAG_V, synth.BF16)
+    o, lse = gu.run_hip(q, k, v, synth.BF16, synth.F32, True, 0.0)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, synth.BF16, True, 0.0)
+    gu.check(o, lse, o_ref, lse_ref, "scale0")
+    np.testing.assert_allclose(lse[0, 0], np.log(np.arange(1, S + 1)), atol=1e-4)
