@@ -92,6 +92,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="query rows the oracle baseline is timed on (0 = skip)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="only run a plain device copy of this many MiB (5 times): the known-size kernel "
+                         "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by construction (no collectives, no sharding); "
@@ -107,6 +110,17 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     nb.lib()  # fail loudly if the HIP library is missing
+
+    if args.calibrate_copy > 0:
+        n = args.calibrate_copy * (1 << 20)
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 5}))
+        return 0
 
     w = synth.WORKLOADS[args.workload]
     q, k, v = synth.make_inputs(w)

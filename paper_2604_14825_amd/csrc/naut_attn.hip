@@ -53,6 +53,7 @@ constexpr int BM = 128;  // queries per work-group
 constexpr int BN = 64;   // keys per step
 constexpr int NWAVES = 4;
 constexpr int NTHREADS = NWAVES * 64;
+constexpr float RESCALE_TAU = 6.0f;  // log2 units
 
 struct Params {
     const void* q;
@@ -163,6 +164,17 @@ __device__ __forceinline__ i32x4_t load_vt_frag(const unsigned char* vt, int kba
     }
 }
 
+// max over the two 32-lane halves.  v_permlane32_swap exchanges the upper 32 lanes of its first
+// operand with the lower 32 lanes of its second, so afterwards (a, b) = (x[lane%32], x[lane%32+32])
+// in every lane.  Written as inline asm: the compiler folds the two results of the corresponding
+// builtin into one.
+__device__ __forceinline__ float half_max(float x)
+{
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return fmaxf(a, b);
+}
+
 // ---- the kernel ------------------------------------------------------------------
 
 template <int D, int DT_IN, int DT_OUT, bool CAUSAL, bool VTR>
@@ -209,6 +221,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
         qf[ks] = *(const i32x4_t*)(qg + (size_t)my_q_ld * ROWB + ks * 32 + h * 16);
+    // Keep Q resident: without this the compiler re-issues the global loads inside the key loop.
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        asm volatile("" : "+v"(qf[ks]));
 
     const int kv_end = CAUSAL ? (S < (qt + 1) * BM ? S : (qt + 1) * BM) : S;
     const int ntiles = (kv_end + BN - 1) / BN;
@@ -294,10 +310,24 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     mx = fmaxf(mx, sacc[kb][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx * c);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // repair factor
-            m_run = m_new;
+            mx = half_max(mx);
+            // The reference maximum only has to be *a* bound shared by l and O, not the exact running
+            // maximum: it is moved (and the partial sums repaired) only when some query of this
+            // wavefront exceeds it by more than 2^RESCALE_TAU, which keeps every P below that factor.
+            const float m_cand = mx * c;
+            const bool grow = m_cand > m_run + RESCALE_TAU;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float m_new = fmaxf(m_run, m_cand);
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // repair factor
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        oacc[db][r] *= alpha;
+            }
+            const float m_new = m_run;
             float psum = 0.f;
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
@@ -307,12 +337,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
                     sacc[kb][r] = pv;
                     psum += pv;
                 }
-            l_run = l_run * alpha + psum;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    oacc[db][r] *= alpha;
+            l_run += psum;
             // O^T += V^T . P^T, 16 keys per MFMA
 #pragma unroll
             for (int t = 0; t < BN / 16; ++t) {
