@@ -31,6 +31,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 #include "naut_attn.h"
 
@@ -62,7 +63,8 @@ struct Params {
     void* o;
     float* lse;
     int B, Hq, Hkv, S;
-    int nqt;       // number of query tiles = ceil(S / BM)
+    int nqt;       // number of 128-query tiles = ceil(S / BM)
+    int nqt2;      // number of 256-query tiles
     float c;       // scale * log2(e), > 0
 };
 
@@ -382,6 +384,406 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
     }
 }
 
+// ---- kernel 2: 64 queries per wavefront, software-pipelined over 32-key blocks -------------
+//
+// A work-group owns 256 queries (4 wavefronts x 64); each lane owns two queries (one in each
+// 32-query half, "A" and "B").  Every K fragment and every V^T fragment read from LDS feeds two
+// MFMAs (half A and half B), which halves LDS traffic per FLOP compared with 32 queries per
+// wavefront.  With one wavefront per SIMD, matrix and vector work overlap inside the wavefront:
+// the key axis is processed in 32-key blocks and stage k issues
+//
+//     MFMA:  Y(k-1) = O^T += V^T . P^T of block k-1      VALU:  SM(k) = online softmax of block k
+//            X(k+1) = S^T of block k+1
+//
+// so the MFMAs of a stage never depend on its vector work.  K and V tiles (64 keys) are
+// triple-buffered in LDS and filled by direct global->LDS loads, one barrier per tile.
+
+constexpr int BM2 = 256;
+constexpr int NBUF = 3;
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// sum over the two 32-lane halves (same exchange as half_max)
+__device__ __forceinline__ float half_sum(float x)
+{
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
+}
+
+template <int D, int DT_IN, int DT_OUT, bool CAUSAL>
+__global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p)
+{
+    using T = In<DT_IN>;
+    constexpr int ROWB = D * 2;
+    constexpr int TILEB = BN * ROWB;           // one 64-key K or V tile
+    constexpr int CPR = D / 8;
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int LD_PER_W = TILEB / 1024 / NWAVES;  // direct loads per wavefront per tile (1 KB each)
+
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * TILEB];  // K0 K1 K2 V0 V1 V2
+    unsigned char* const k_lds = smem;
+    unsigned char* const v_lds = smem + NBUF * TILEB;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+
+    const int nbh = p.B * p.Hq;
+    const int bid = blockIdx.x;
+    const int qt = p.nqt2 - 1 - bid / nbh;   // heaviest query tiles first
+    const int bh = bid % nbh;
+    const int b = bh / p.Hq;
+    const int hq = bh % p.Hq;
+    const int hk = hq / (p.Hq / p.Hkv);
+    const int S = p.S;
+    const float c = p.c;
+
+    const unsigned char* qg = (const unsigned char*)p.q + (size_t)bh * S * ROWB;
+    const unsigned char* kg = (const unsigned char*)p.k + (size_t)(b * p.Hkv + hk) * S * ROWB;
+    const unsigned char* vg = (const unsigned char*)p.v + (size_t)(b * p.Hkv + hk) * S * ROWB;
+
+    const int Q0 = qt * BM2 + wave * 64;  // first query of this wavefront
+    const int qa = Q0 + l32, qb = Q0 + 32 + l32;
+
+    // Q^T fragments of both halves (MFMA B operands), resident for the whole kernel.
+    i32x4_t qfa[KS], qfb[KS];
+    {
+        const int qa_ld = qa < S ? qa : S - 1, qb_ld = qb < S ? qb : S - 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qfa[ks] = *(const i32x4_t*)(qg + (size_t)qa_ld * ROWB + ks * 32 + h * 16);
+            qfb[ks] = *(const i32x4_t*)(qg + (size_t)qb_ld * ROWB + ks * 32 + h * 16);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            asm volatile("" : "+v"(qfa[ks]));
+            asm volatile("" : "+v"(qfb[ks]));
+        }
+    }
+
+    // Key blocks (32 keys) this wavefront / this work-group has to visit.
+    const int kv_end_wg = CAUSAL ? (S < (qt + 1) * BM2 ? S : (qt + 1) * BM2) : S;
+    const int kv_end_w = Q0 >= S ? 0 : (CAUSAL ? (S < Q0 + 64 ? S : Q0 + 64) : S);
+    const int nb_w = (kv_end_w + 31) >> 5;
+    const int nb_wg = (kv_end_wg + 31) >> 5;
+    const int ntiles = (kv_end_wg + BN - 1) / BN;
+    const int niter = (nb_wg + 2) >> 1;  // stages 0..nb_wg, two per iteration
+
+    // Direct global->LDS tile loads.  Each instruction moves 1 KB: lane i fills physical chunk i of
+    // the block, so the lane fetches the logical chunk that the swizzle maps there.
+    int k_goff[LD_PER_W], v_goff[LD_PER_W], k_grow[LD_PER_W], v_grow[LD_PER_W];
+#pragma unroll
+    for (int i = 0; i < LD_PER_W; ++i) {
+        const int P = (wave * LD_PER_W + i) * 64 + lane;  // physical chunk index in the tile
+        {
+            const int line = P >> 4, pos = P & 15;
+            const int L = (line << 4) + (pos ^ (line & 15));
+            k_grow[i] = L / CPR;
+            k_goff[i] = (L % CPR) * 16;
+        }
+        if constexpr (D == 128) {
+            const int row = P >> 4, cc = P & 15;
+            v_grow[i] = row;
+            v_goff[i] = (cc ^ ((row & 3) << 2)) * 16;
+        } else {
+            const int row = P >> 3, cc = P & 7;
+            v_grow[i] = row;
+            v_goff[i] = (cc ^ (((row >> 1) & 1) << 2)) * 16;
+        }
+    }
+    auto load_tile = [&](const unsigned char* g, unsigned char* lds_tiles, int tile, const int* grow, const int* goff) {
+        unsigned char* dst = lds_tiles + (tile % NBUF) * TILEB + wave * LD_PER_W * 1024;
+#pragma unroll
+        for (int i = 0; i < LD_PER_W; ++i) {
+            int row = tile * BN + grow[i];
+            row = row < S ? row : S - 1;
+            const unsigned char* src = g + (size_t)row * ROWB + goff[i];
+            // Written as asm so that the compiler does not make every later LDS read wait for these
+            // loads; completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
+            const unsigned lds_addr = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)(dst + i * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :
+                         : "s"(lds_addr), "v"(src)
+                         : "memory", "m0");
+        }
+    };
+
+    f32x16_t oa[DB], ob[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            oa[db][r] = 0.f;
+            ob[db][r] = 0.f;
+        }
+    float ma = -INFINITY, mb = -INFINITY, la = 0.f, lb = 0.f;
+
+    // ---- pipeline pieces ----
+    // X(kblk): S^T of 32-key block kblk for both halves.
+    auto stage_x = [&](int kblk, f32x16_t& sa, f32x16_t& sb) {
+        const unsigned char* kt = k_lds + ((kblk >> 1) % NBUF) * TILEB;
+        const int row = (kblk & 1) * 32 + l32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            sa[r] = 0.f;
+            sb[r] = 0.f;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const i32x4_t kf = *(const i32x4_t*)(kt + k_off<D>(row, ks * 2 + h));
+            sa = T::mfma(kf, qfa[ks], sa);
+            sb = T::mfma(kf, qfb[ks], sb);
+        }
+    };
+    // Y(kblk): O^T += V^T . P^T over the 32 keys of block kblk.
+    auto stage_y = [&](int kblk, const i32x4_t (&pa)[2], const i32x4_t (&pb)[2]) {
+        const unsigned char* vt = v_lds + ((kblk >> 1) % NBUF) * TILEB;
+        const int kbase = (kblk & 1) * 32;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const i32x4_t vf = load_vt_frag<D, true>(vt, kbase + 16 * t, db, lane);
+                oa[db] = T::mfma(vf, pa[t], oa[db]);
+                ob[db] = T::mfma(vf, pb[t], ob[db]);
+            }
+    };
+    // SM(kblk), first part: masking (if asked) and the new reference maxima / repair factors.
+    auto mask_block = [&](int kblk, f32x16_t& sa, f32x16_t& sb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = kblk * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+            const bool oob = key >= kv_end_w;  // beyond the sequence, or beyond this wavefront's last block
+            sa[r] = (oob || (CAUSAL && key > qa)) ? -INFINITY : sa[r];
+            sb[r] = (oob || (CAUSAL && key > qb)) ? -INFINITY : sb[r];
+        }
+    };
+    auto row_max16 = [&](const f32x16_t& s) {
+        float m0 = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2)
+            m0 = fmaxf(m0, fmaxf(s[r], s[r + 1]));
+        return half_max(m0);
+    };
+    // exponentials, row sums and the packed P^T operands of one half
+    auto exp_pack = [&](f32x16_t& s, float m_new, float& psum, i32x4_t (&pp)[2]) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -m_new));
+            psum += s[r];
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            i32x4_t w = {T::pack2(s[8 * t + 0], s[8 * t + 1]), T::pack2(s[8 * t + 2], s[8 * t + 3]),
+                         T::pack2(s[8 * t + 4], s[8 * t + 5]), T::pack2(s[8 * t + 6], s[8 * t + 7])};
+            pp[t] = w;
+        }
+    };
+
+    // One pipeline stage k: Y(k-1) and X(k+1) on the matrix pipe, SM(k) on the vector ALU.  Every
+    // wavefront runs every stage: Y(-1) is issued with P = 0, X past the last block computes scores
+    // nobody reads, and SM of a block past this wavefront's last one is fully masked (P = 0, no
+    // change of m or l), so one straight-line body serves every k and the loop has a single path.
+    //
+    // The body is written as 2*KS "units" of two MFMAs (one LDS fragment feeding half A and half B),
+    // alternating Y and X units, each followed by a slice of the softmax arithmetic; scheduling
+    // fences between units keep that interleaving (and keep LDS reads just two units ahead of their
+    // use, which bounds the registers they occupy).
+    auto stage = [&](int k, bool masked, f32x16_t& sa_cur, f32x16_t& sb_cur, f32x16_t& sa_nxt, f32x16_t& sb_nxt,
+                     const i32x4_t (&pa_in)[2], const i32x4_t (&pb_in)[2], i32x4_t (&pa_out)[2],
+                     i32x4_t (&pb_out)[2]) {
+        if (masked)
+            mask_block(k, sa_cur, sb_cur);
+        constexpr int NU = 2 * KS;       // units: even = Y (V^T fragment), odd = X (K fragment)
+        constexpr int NYU = 2 * DB;      // Y units that exist (== KS for D = 128 and D = 64)
+        static_assert(NYU == KS, "Y and X units must pair up");
+        int ky = k > 0 ? k - 1 : 0;       // stage 0 has P = 0; past the end P = 0 as well
+        ky = ky < nb_wg ? ky : nb_wg - 1;  // stay on a V tile that is resident
+        const unsigned char* vt = v_lds + ((ky >> 1) % NBUF) * TILEB;
+        const int vkbase = (ky & 1) * 32;
+        const unsigned char* kt = k_lds + (((k + 1) >> 1) % NBUF) * TILEB;
+        const int krow = ((k + 1) & 1) * 32 + l32;
+        i32x4_t frag[NU];
+        auto issue = [&](auto U) {
+            constexpr int u = decltype(U)::value;
+            if constexpr (u % 2 == 0) {
+                constexpr int i = u / 2;
+                frag[u] = load_vt_frag<D, true>(vt, vkbase + 16 * (i / DB), i % DB, lane);
+            } else {
+                constexpr int ks = u / 2;
+                frag[u] = *(const i32x4_t*)(kt + k_off<D>(krow, ks * 2 + h));
+            }
+        };
+        float mxa = 0.f, mxb = 0.f, ca = 0.f, cb = 0.f, ma_new = 0.f, mb_new = 0.f, psa = 0.f, psb = 0.f;
+        bool any = false;
+        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // softmax slices: 4 for the maxima, the rest for the 32 exponentials (16 per half)
+        constexpr int NEXPU = NU - 4;
+        auto exp_one = [&](f32x16_t& s_, float m_new, float& psum, i32x4_t (&pp)[2], int e) {
+            s_[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[e], c, -m_new));
+            psum += s_[e];
+            if (e & 1) {
+                int w = T::pack2(s_[e - 1], s_[e]);
+                // anchor: keeps this slice of the softmax inside its unit (the optimiser would
+                // otherwise sink it to the first use of P, after the last MFMA of the stage)
+                asm volatile("" : "+v"(w), "+v"(psum));
+                pp[e >> 3][(e >> 1) & 3] = w;
+            }
+        };
+        auto valu = [&](auto U) {
+            constexpr int u = decltype(U)::value;
+            if constexpr (u == 0) {
+                mxa = fmaxf(sa_cur[0], sa_cur[1]);
+#pragma unroll
+                for (int r = 2; r < 16; r += 2)
+                    mxa = fmaxf(mxa, fmaxf(sa_cur[r], sa_cur[r + 1]));
+            } else if constexpr (u == 1) {
+                mxb = fmaxf(sb_cur[0], sb_cur[1]);
+#pragma unroll
+                for (int r = 2; r < 16; r += 2)
+                    mxb = fmaxf(mxb, fmaxf(sb_cur[r], sb_cur[r + 1]));
+            } else if constexpr (u == 2) {
+                ca = half_max(mxa) * c;
+                cb = half_max(mxb) * c;
+            } else if constexpr (u == 3) {
+                const bool grow = (ca > ma + RESCALE_TAU) || (cb > mb + RESCALE_TAU);
+                any = __builtin_amdgcn_ballot_w64(grow) != 0;
+                ma_new = any ? fmaxf(ma, ca) : ma;
+                mb_new = any ? fmaxf(mb, cb) : mb;
+            } else {
+                constexpr int i = u - 4;
+                constexpr int e0 = i * 32 / NEXPU, e1 = (i + 1) * 32 / NEXPU;
+#pragma unroll
+                for (int e = e0; e < e1; ++e) {
+                    if (e < 16)
+                        exp_one(sa_cur, ma_new, psa, pa_out, e);
+                    else
+                        exp_one(sb_cur, mb_new, psb, pb_out, e - 16);
+                }
+            }
+        };
+        issue(std::integral_constant<int, 0>{});
+        issue(std::integral_constant<int, 1>{});
+        static_for<0, NU>([&](auto U) {
+            constexpr int u = decltype(U)::value;
+            if constexpr (u + 2 < NU)
+                issue(std::integral_constant<int, u + 2>{});
+            if constexpr (u % 2 == 0) {
+                constexpr int i = u / 2, t = i / DB, db = i % DB;
+                oa[db] = T::mfma(frag[u], pa_in[t], oa[db]);
+                ob[db] = T::mfma(frag[u], pb_in[t], ob[db]);
+            } else {
+                constexpr int ks = u / 2;
+                sa_nxt = T::mfma(frag[u], qfa[ks], ks == 0 ? zero16 : sa_nxt);
+                sb_nxt = T::mfma(frag[u], qfb[ks], ks == 0 ? zero16 : sb_nxt);
+            }
+            valu(U);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (any) {
+            // repair factors; applied after Y(k-1), whose P was formed against the old maxima
+            const float aa = __builtin_amdgcn_exp2f(ma - ma_new), ab = __builtin_amdgcn_exp2f(mb - mb_new);
+            la *= aa;
+            lb *= ab;
+            // One accumulator block at a time; each block is pinned back into the accumulation
+            // registers right away so that O never lives in ordinary vector registers in the loop.
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    oa[db][r] *= aa;
+                asm volatile("" : "+a"(oa[db]));
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    ob[db][r] *= ab;
+                asm volatile("" : "+a"(ob[db]));
+            }
+            ma = ma_new;
+            mb = mb_new;
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            asm volatile("" : "+a"(oa[db]), "+a"(ob[db]));
+        la += psa;
+        lb += psb;
+    };
+    auto needs_mask = [&](int k) { return (CAUSAL && 32 * k + 31 > Q0) || 32 * k + 32 > kv_end_w; };
+
+    // ---- prologue: K tiles 0 and 1, V tile 0; S of block 0 ----
+    load_tile(kg, k_lds, 0, k_grow, k_goff);
+    load_tile(vg, v_lds, 0, v_grow, v_goff);
+    if (ntiles > 1)
+        load_tile(kg, k_lds, 1, k_grow, k_goff);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    f32x16_t s0a, s0b, s1a, s1b;
+    i32x4_t pea[2], peb[2], poa[2], pob[2];  // P of the last even / odd block
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        pea[t] = i32x4_t{0, 0, 0, 0};
+        peb[t] = i32x4_t{0, 0, 0, 0};
+        poa[t] = i32x4_t{0, 0, 0, 0};
+        pob[t] = i32x4_t{0, 0, 0, 0};
+    }
+    stage_x(0, s0a, s0b);
+
+    for (int j = 0; j < niter; ++j) {
+        if (j + 2 < ntiles)
+            load_tile(kg, k_lds, j + 2, k_grow, k_goff);
+        if (j + 1 < ntiles)
+            load_tile(vg, v_lds, j + 1, v_grow, v_goff);
+
+        const int ke = 2 * j, ko = 2 * j + 1;
+        stage(ke, needs_mask(ke), s0a, s0b, s1a, s1b, poa, pob, pea, peb);
+        stage(ko, needs_mask(ko), s1a, s1b, s0a, s0b, pea, peb, poa, pob);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+
+    // ---- epilogue ----
+    if (Q0 >= S)
+        return;
+    const float lta = half_sum(la), ltb = half_sum(lb);
+    constexpr int OUTB = DT_OUT == NAUT_F32 ? 4 : 2;
+    auto store_half = [&](int q, float m, float lt, const f32x16_t (&o)[DB]) {
+        if (q >= S)
+            return;
+        const float inv_l = 1.0f / lt;
+        if (p.lse != nullptr && h == 0)
+            p.lse[(size_t)bh * S + q] = (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
+        unsigned char* og = (unsigned char*)p.o + ((size_t)bh * S + q) * D * OUTB;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int d = 32 * db + 8 * g + 4 * h;
+                const float x0 = o[db][4 * g + 0] * inv_l, x1 = o[db][4 * g + 1] * inv_l;
+                const float x2 = o[db][4 * g + 2] * inv_l, x3 = o[db][4 * g + 3] * inv_l;
+                if constexpr (DT_OUT == NAUT_F32) {
+                    f32x4_t w = {x0, x1, x2, x3};
+                    *(f32x4_t*)(og + d * 4) = w;
+                } else {
+                    i32x2_t w = {In<DT_OUT>::pack2(x0, x1), In<DT_OUT>::pack2(x2, x3)};
+                    *(i32x2_t*)(og + d * 2) = w;
+                }
+            }
+    };
+    store_half(qa, ma, lta, oa);
+    store_half(qb, mb, ltb, ob);
+}
+
 // ---- host side ---------------------------------------------------------------------
 
 thread_local char g_err[256] = "";
@@ -398,6 +800,12 @@ bool use_vtr()
     return e == nullptr || e[0] != '0';
 }
 
+int kernel_choice()
+{
+    const char* e = getenv("NAUT_ATTN_KERNEL");
+    return e == nullptr ? 2 : atoi(e);
+}
+
 template <int D, int DT_IN, int DT_OUT>
 int launch(const Params& p, int causal, hipStream_t stream)
 {
@@ -406,7 +814,13 @@ int launch(const Params& p, int causal, hipStream_t stream)
         return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");
     const dim3 grid((unsigned)nblocks), block(NTHREADS);
     const bool vtr = use_vtr();
-    if (causal) {
+    if (kernel_choice() == 2) {
+        const dim3 grid2((unsigned)((long long)p.nqt2 * p.B * p.Hq));
+        if (causal)
+            hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, true>), grid2, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, false>), grid2, block, 0, stream, p);
+    } else if (causal) {
         if (vtr)
             hipLaunchKernelGGL((naut_fwd_kernel<D, DT_IN, DT_OUT, true, true>), grid, block, 0, stream, p);
         else
@@ -471,6 +885,7 @@ int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float
     p.Hkv = Hkv;
     p.S = S;
     p.nqt = (S + BM - 1) / BM;
+    p.nqt2 = (S + BM2 - 1) / BM2;
     // exp(x) = exp2(log2(e) x); the constant is hoisted out of the key loop.  A zero scale is
     // replaced by the smallest useful positive constant so that masked scores (-inf) stay -inf.
     const float c = scale * 1.4426950408889634f;
