@@ -395,11 +395,26 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
 //     MFMA:  Y(k-1) = O^T += V^T . P^T of block k-1      VALU:  SM(k) = online softmax of block k
 //            X(k+1) = S^T of block k+1
 //
-// so the MFMAs of a stage never depend on its vector work.  K and V tiles (64 keys) are
-// triple-buffered in LDS and filled by direct global->LDS loads, one barrier per tile.
+// so the MFMAs of a stage never depend on its vector work.  A stage is laid out as a sequence of
+// slots, one MFMA each, followed by a few vector instructions: the matrix pipe hides about six
+// ordinary vector instructions per MFMA and no more, so the softmax is cut into pieces of that
+// size.  K and V tiles (64 keys) are triple-buffered in LDS and filled by direct global->LDS loads
+// issued two tiles ahead, one barrier per tile.
 
+#ifndef NAUT_ABLATE
+#define NAUT_ABLATE 0
+#endif
+constexpr int ABL = NAUT_ABLATE;  // timing experiments only: 1 = no softmax pieces, 2 = no LDS reads, 4 = no barrier, 8 = no tile loads, 16 = trace, 32 = no V^T reads, 64 = no K reads
 constexpr int BM2 = 256;
-constexpr int NBUF = 3;
+#ifndef NAUT_LA
+#define NAUT_LA 2
+#endif
+#ifndef NAUT_PF
+#define NAUT_PF 3
+#endif
+constexpr int LA = NAUT_LA;     // tile loads are issued this many iterations ahead of their use
+constexpr int NBUF = LA + 1;    // LDS buffers per operand
+constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no maximum yet": keeps -inf - (-inf) out
 
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for(F&& f)
@@ -418,20 +433,86 @@ __device__ __forceinline__ float half_sum(float x)
     return a + b;
 }
 
+// S^T MFMAs written as asm so that their accumulator is an ordinary vector register tuple: the
+// softmax reads every score, and the compiler's own MFMA form would put the scores in the
+// accumulation registers and copy each one out.  Operands never come straight from a vector
+// instruction (A: LDS read, B: resident Q in the accumulation registers, C: an MFMA two slots earlier), and the scores are read
+// a whole stage later, so no software wait states are owed around these.
+template <int DT>
+struct XMfma;
+template <>
+struct XMfma<NAUT_BF16> {
+    static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+    }
+    static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+    }
+    static __device__ __forceinline__ float dot2acc(int packed, float acc)
+    {
+        const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, packed), ones, acc, false);
+    }
+};
+template <>
+struct XMfma<NAUT_F16> {
+    static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+    }
+    static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+    }
+    static __device__ __forceinline__ float dot2acc(int packed, float acc)
+    {
+        const f16x2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, packed), ones, acc, false);
+    }
+};
+
+// The softmax of a stage is cut into NPIECE pieces (8 for the maxima, one per exponential) whose
+// approximate issue costs, in 4-cycle vector slots (an exponential counts 2), are given here; they
+// are dealt out to the MFMA slots greedily, at most `cap` per slot, in order.
+constexpr int NPIECE = 40;
+constexpr int piece_cost(int pc) { return pc < 6 ? 4 : pc == 6 ? 4 : pc == 7 ? 5 : ((pc - 8) % 2 == 0 ? 4 : 5); }
+template <int NSLOT>
+constexpr int piece_begin(int slot)
+{
+    int total = 0;
+    for (int pc = 0; pc < NPIECE; ++pc)
+        total += piece_cost(pc);
+    const int cap = (total + NSLOT - 1) / NSLOT + 1;
+    int pc = 0;
+    for (int s = 0; s < slot && s < NSLOT; ++s) {
+        int used = 0;
+        // the last slot takes whatever is left
+        while (pc < NPIECE && (s == NSLOT - 1 || used + piece_cost(pc) <= cap || used == 0)) {
+            used += piece_cost(pc);
+            ++pc;
+        }
+    }
+    return slot >= NSLOT ? NPIECE : pc;
+}
+
 template <int D, int DT_IN, int DT_OUT, bool CAUSAL>
 __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p)
 {
     using T = In<DT_IN>;
+    using XM = XMfma<DT_IN>;
     constexpr int ROWB = D * 2;
     constexpr int TILEB = BN * ROWB;           // one 64-key K or V tile
     constexpr int CPR = D / 8;
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
     constexpr int LD_PER_W = TILEB / 1024 / NWAVES;  // direct loads per wavefront per tile (1 KB each)
+    constexpr int NF = 2 * KS;                 // fragments per stage: even = V^T (Y), odd = K (X)
+    constexpr int NS = 2 * NF;                 // slots (MFMAs) per stage
+    static_assert(2 * DB == KS, "Y and X fragments must pair up");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * TILEB];  // K0 K1 K2 V0 V1 V2
-    unsigned char* const k_lds = smem;
-    unsigned char* const v_lds = smem + NBUF * TILEB;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -467,57 +548,78 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            asm volatile("" : "+v"(qfa[ks]));
-            asm volatile("" : "+v"(qfb[ks]));
+            asm volatile("" : "+a"(qfa[ks]));  // Q lives in the accumulation registers (MFMA B operand)
+            asm volatile("" : "+a"(qfb[ks]));
         }
     }
 
-    // Key blocks (32 keys) this wavefront / this work-group has to visit.
+    // Key range of this wavefront / this work-group (keys at or beyond kv_end_w are dead for it).
     const int kv_end_wg = CAUSAL ? (S < (qt + 1) * BM2 ? S : (qt + 1) * BM2) : S;
     const int kv_end_w = Q0 >= S ? 0 : (CAUSAL ? (S < Q0 + 64 ? S : Q0 + 64) : S);
-    const int nb_w = (kv_end_w + 31) >> 5;
-    const int nb_wg = (kv_end_wg + 31) >> 5;
     const int ntiles = (kv_end_wg + BN - 1) / BN;
-    const int niter = (nb_wg + 2) >> 1;  // stages 0..nb_wg, two per iteration
+    const int niter = ntiles + 1;  // stages -1 .. 2*ntiles, two per iteration
 
     // Direct global->LDS tile loads.  Each instruction moves 1 KB: lane i fills physical chunk i of
-    // the block, so the lane fetches the logical chunk that the swizzle maps there.
-    int k_goff[LD_PER_W], v_goff[LD_PER_W], k_grow[LD_PER_W], v_grow[LD_PER_W];
+    // the block, so the lane fetches the logical chunk that the swizzle maps there.  The address is
+    // (scalar tile base) + (per-lane constant offset), so a full tile costs no vector arithmetic.
+    int k_goff[LD_PER_W], v_goff[LD_PER_W];  // byte offset of the lane's chunk inside a tile
 #pragma unroll
     for (int i = 0; i < LD_PER_W; ++i) {
         const int P = (wave * LD_PER_W + i) * 64 + lane;  // physical chunk index in the tile
         {
             const int line = P >> 4, pos = P & 15;
             const int L = (line << 4) + (pos ^ (line & 15));
-            k_grow[i] = L / CPR;
-            k_goff[i] = (L % CPR) * 16;
+            k_goff[i] = L * 16;  // rows are contiguous in memory: row * ROWB + chunk * 16 == L * 16
         }
         if constexpr (D == 128) {
             const int row = P >> 4, cc = P & 15;
-            v_grow[i] = row;
-            v_goff[i] = (cc ^ ((row & 3) << 2)) * 16;
+            v_goff[i] = row * ROWB + (cc ^ ((row & 3) << 2)) * 16;
         } else {
             const int row = P >> 3, cc = P & 7;
-            v_grow[i] = row;
-            v_goff[i] = (cc ^ (((row >> 1) & 1) << 2)) * 16;
+            v_goff[i] = row * ROWB + (cc ^ (((row >> 1) & 1) << 2)) * 16;
         }
     }
-    auto load_tile = [&](const unsigned char* g, unsigned char* lds_tiles, int tile, const int* grow, const int* goff) {
-        unsigned char* dst = lds_tiles + (tile % NBUF) * TILEB + wave * LD_PER_W * 1024;
+    const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
+    // tile index is clamped so that every call issues the same number of loads (the vmcnt
+    // arithmetic below counts on it); a clamped reload lands in a buffer nobody reads.
+    auto load_tile = [&](const unsigned char* g, unsigned lds_tiles, int tile, const int* goff) {
+        const int tl = tile < ntiles ? tile : ntiles - 1;
+        const unsigned dst = lds_tiles + (unsigned)((tile % NBUF) * TILEB + wave * LD_PER_W * 1024);
+        const unsigned char* gt = g + ((ABL & 128) ? (size_t)0 : (size_t)tl * TILEB);  // wave-uniform
+        const int rows_left = S - tl * BN;                 // rows of this tile that exist
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i) {
-            int row = tile * BN + grow[i];
-            row = row < S ? row : S - 1;
-            const unsigned char* src = g + (size_t)row * ROWB + goff[i];
-            // Written as asm so that the compiler does not make every later LDS read wait for these
-            // loads; completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
-            const unsigned lds_addr = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)(dst + i * 1024);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+            int off = goff[i];
+            if constexpr ((ABL & 128) != 0)
+                off = 0;  // timing experiment: every lane reads the same 16 bytes
+            if (rows_left < BN) {  // ragged last tile: re-read the last row instead of running past the end
+                const int row = off / ROWB;
+                off = row < rows_left ? off : (rows_left - 1) * ROWB + off % ROWB;
+            }
+            // asm, so that the compiler does not make every later LDS read wait for these loads;
+            // completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
-                         : "s"(lds_addr), "v"(src)
+                         : "s"(dst + i * 1024), "v"(off), "s"(gt)
                          : "memory", "m0");
         }
     };
+    const unsigned k_lds = smem_base, v_lds = smem_base + NBUF * TILEB;
+
+    // Lane parts of the LDS fragment addresses (block / step offsets are immediates on top).
+    int k_lane[KS], v_lane[DB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        k_lane[ks] = k_off<D>(l32, ks * 2 + h);
+    {
+        const int i16 = lane & 15;
+        const int key = 4 * h + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int d = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+            v_lane[db] = v_off<D>(key, d >> 3) + (d & 7) * 2;
+        }
+    }
 
     f32x16_t oa[DB], ob[DB];
 #pragma unroll
@@ -527,168 +629,152 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
             oa[db][r] = 0.f;
             ob[db][r] = 0.f;
         }
-    float ma = -INFINITY, mb = -INFINITY, la = 0.f, lb = 0.f;
+    float ma = M_INIT, mb = M_INIT, la = 0.f, lb = 0.f;
 
-    // ---- pipeline pieces ----
-    // X(kblk): S^T of 32-key block kblk for both halves.
-    auto stage_x = [&](int kblk, f32x16_t& sa, f32x16_t& sb) {
-        const unsigned char* kt = k_lds + ((kblk >> 1) % NBUF) * TILEB;
-        const int row = (kblk & 1) * 32 + l32;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            sa[r] = 0.f;
-            sb[r] = 0.f;
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const i32x4_t kf = *(const i32x4_t*)(kt + k_off<D>(row, ks * 2 + h));
-            sa = T::mfma(kf, qfa[ks], sa);
-            sb = T::mfma(kf, qfb[ks], sb);
-        }
-    };
-    // Y(kblk): O^T += V^T . P^T over the 32 keys of block kblk.
-    auto stage_y = [&](int kblk, const i32x4_t (&pa)[2], const i32x4_t (&pb)[2]) {
-        const unsigned char* vt = v_lds + ((kblk >> 1) % NBUF) * TILEB;
-        const int kbase = (kblk & 1) * 32;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const i32x4_t vf = load_vt_frag<D, true>(vt, kbase + 16 * t, db, lane);
-                oa[db] = T::mfma(vf, pa[t], oa[db]);
-                ob[db] = T::mfma(vf, pb[t], ob[db]);
-            }
-    };
-    // SM(kblk), first part: masking (if asked) and the new reference maxima / repair factors.
+    // SM(kblk) part 0: causal / tail / out-of-range masking
     auto mask_block = [&](int kblk, f32x16_t& sa, f32x16_t& sb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int key = kblk * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            const bool oob = key >= kv_end_w;  // beyond the sequence, or beyond this wavefront's last block
+            const bool oob = key >= kv_end_w || kblk < 0;
             sa[r] = (oob || (CAUSAL && key > qa)) ? -INFINITY : sa[r];
             sb[r] = (oob || (CAUSAL && key > qb)) ? -INFINITY : sb[r];
         }
     };
-    auto row_max16 = [&](const f32x16_t& s) {
-        float m0 = fmaxf(s[0], s[1]);
-#pragma unroll
-        for (int r = 2; r < 16; r += 2)
-            m0 = fmaxf(m0, fmaxf(s[r], s[r + 1]));
-        return half_max(m0);
-    };
-    // exponentials, row sums and the packed P^T operands of one half
-    auto exp_pack = [&](f32x16_t& s, float m_new, float& psum, i32x4_t (&pp)[2]) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -m_new));
-            psum += s[r];
-        }
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            i32x4_t w = {T::pack2(s[8 * t + 0], s[8 * t + 1]), T::pack2(s[8 * t + 2], s[8 * t + 3]),
-                         T::pack2(s[8 * t + 4], s[8 * t + 5]), T::pack2(s[8 * t + 6], s[8 * t + 7])};
-            pp[t] = w;
-        }
-    };
+    auto needs_mask = [&](int k) { return k < 0 || (CAUSAL && 32 * k + 31 > Q0) || 32 * k + 32 > kv_end_w; };
 
-    // One pipeline stage k: Y(k-1) and X(k+1) on the matrix pipe, SM(k) on the vector ALU.  Every
-    // wavefront runs every stage: Y(-1) is issued with P = 0, X past the last block computes scores
-    // nobody reads, and SM of a block past this wavefront's last one is fully masked (P = 0, no
-    // change of m or l), so one straight-line body serves every k and the loop has a single path.
-    //
-    // The body is written as 2*KS "units" of two MFMAs (one LDS fragment feeding half A and half B),
-    // alternating Y and X units, each followed by a slice of the softmax arithmetic; scheduling
-    // fences between units keep that interleaving (and keep LDS reads just two units ahead of their
-    // use, which bounds the registers they occupy).
-    auto stage = [&](int k, bool masked, f32x16_t& sa_cur, f32x16_t& sb_cur, f32x16_t& sa_nxt, f32x16_t& sb_nxt,
-                     const i32x4_t (&pa_in)[2], const i32x4_t (&pb_in)[2], i32x4_t (&pa_out)[2],
-                     i32x4_t (&pb_out)[2]) {
-        if (masked)
+    // One pipeline stage k = 2*j - 1 + BLK of iteration j: Y(k-1) reads block BLK of the V tile in
+    // v_it, X(k+1) block BLK of the K tile in k_it.  Every wavefront runs every stage: blocks that
+    // do not exist for it are fully masked in SM (P = 0, m and l unchanged), Y then adds zeros and
+    // X computes scores nobody reads, so one straight-line body serves every k.
+    auto stage = [&](auto BLKC, int k, const int (&k_it)[KS], const int (&v_it)[DB], f32x16_t& sa_cur,
+                     f32x16_t& sb_cur, f32x16_t& sa_nxt, f32x16_t& sb_nxt, const i32x4_t (&pa_in)[2],
+                     const i32x4_t (&pb_in)[2], i32x4_t (&pa_out)[2], i32x4_t (&pb_out)[2]) {
+        constexpr int BLK = decltype(BLKC)::value;
+        if (needs_mask(k))
             mask_block(k, sa_cur, sb_cur);
-        constexpr int NU = 2 * KS;       // units: even = Y (V^T fragment), odd = X (K fragment)
-        constexpr int NYU = 2 * DB;      // Y units that exist (== KS for D = 128 and D = 64)
-        static_assert(NYU == KS, "Y and X units must pair up");
-        int ky = k > 0 ? k - 1 : 0;       // stage 0 has P = 0; past the end P = 0 as well
-        ky = ky < nb_wg ? ky : nb_wg - 1;  // stay on a V tile that is resident
-        const unsigned char* vt = v_lds + ((ky >> 1) % NBUF) * TILEB;
-        const int vkbase = (ky & 1) * 32;
-        const unsigned char* kt = k_lds + (((k + 1) >> 1) % NBUF) * TILEB;
-        const int krow = ((k + 1) & 1) * 32 + l32;
-        i32x4_t frag[NU];
-        auto issue = [&](auto U) {
-            constexpr int u = decltype(U)::value;
-            if constexpr (u % 2 == 0) {
-                constexpr int i = u / 2;
-                frag[u] = load_vt_frag<D, true>(vt, vkbase + 16 * (i / DB), i % DB, lane);
+        i32x4_t frag[NF];
+        auto issue = [&](auto F) {
+            constexpr int f = decltype(F)::value;
+            if constexpr ((ABL & 2) || ((ABL & 32) && f % 2 == 0) || ((ABL & 64) && f % 2 == 1)) {
+                asm volatile("" : "=v"(frag[f]));  // timing experiment: register contents as they are
+            } else if constexpr (f % 2 == 0) {
+                constexpr int y = f / 2, t = y / DB, db = y % DB;
+                constexpr int off = (BLK * 32 + 16 * t) * ROWB;
+                const i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(v_it[db] + off));
+                const i16x4_t r1 =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(v_it[db] + off + 8 * ROWB));
+                const i32x2_t lo = __builtin_bit_cast(i32x2_t, r0), hi = __builtin_bit_cast(i32x2_t, r1);
+                frag[f] = i32x4_t{lo.x, lo.y, hi.x, hi.y};
             } else {
-                constexpr int ks = u / 2;
-                frag[u] = *(const i32x4_t*)(kt + k_off<D>(krow, ks * 2 + h));
+                constexpr int ks = f / 2;
+                frag[f] = *(const NAUT_LDS i32x4_t*)(uintptr_t)(k_it[ks] + BLK * 32 * ROWB);
             }
         };
         float mxa = 0.f, mxb = 0.f, ca = 0.f, cb = 0.f, ma_new = 0.f, mb_new = 0.f, psa = 0.f, psb = 0.f;
         bool any = false;
-        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        // softmax slices: 4 for the maxima, the rest for the 32 exponentials (16 per half)
-        constexpr int NEXPU = NU - 4;
-        auto exp_one = [&](f32x16_t& s_, float m_new, float& psum, i32x4_t (&pp)[2], int e) {
-            s_[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[e], c, -m_new));
-            psum += s_[e];
-            if (e & 1) {
-                int w = T::pack2(s_[e - 1], s_[e]);
-                // anchor: keeps this slice of the softmax inside its unit (the optimiser would
-                // otherwise sink it to the first use of P, after the last MFMA of the stage)
-                asm volatile("" : "+v"(w), "+v"(psum));
-                pp[e >> 3][(e >> 1) & 3] = w;
-            }
+        // max of three as one instruction (the compiler's fmaxf adds a quieting instruction per operand)
+        auto max3 = [](float x, float y, float z) {
+            float r;
+            asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
+            return r;
         };
-        auto valu = [&](auto U) {
-            constexpr int u = decltype(U)::value;
-            if constexpr (u == 0) {
-                mxa = fmaxf(sa_cur[0], sa_cur[1]);
-#pragma unroll
-                for (int r = 2; r < 16; r += 2)
-                    mxa = fmaxf(mxa, fmaxf(sa_cur[r], sa_cur[r + 1]));
-            } else if constexpr (u == 1) {
-                mxb = fmaxf(sb_cur[0], sb_cur[1]);
-#pragma unroll
-                for (int r = 2; r < 16; r += 2)
-                    mxb = fmaxf(mxb, fmaxf(sb_cur[r], sb_cur[r + 1]));
-            } else if constexpr (u == 2) {
-                ca = half_max(mxa) * c;
-                cb = half_max(mxb) * c;
-            } else if constexpr (u == 3) {
+        // vector work of the stage, cut into 8 + 32 pieces (costs in piece_cost)
+        auto piece = [&](auto PC) {
+            constexpr int pc = decltype(PC)::value;
+            if constexpr (pc == 0) {
+                mxa = max3(sa_cur[0], sa_cur[1], sa_cur[2]);
+                mxa = max3(mxa, sa_cur[3], sa_cur[4]);
+                mxa = max3(mxa, sa_cur[5], sa_cur[6]);
+                mxa = max3(mxa, sa_cur[7], sa_cur[8]);
+            } else if constexpr (pc == 1) {
+                mxa = max3(mxa, sa_cur[9], sa_cur[10]);
+                mxa = max3(mxa, sa_cur[11], sa_cur[12]);
+                mxa = max3(mxa, sa_cur[13], sa_cur[14]);
+                mxa = max3(mxa, sa_cur[15], sa_cur[15]);
+            } else if constexpr (pc == 2) {
+                mxb = max3(sb_cur[0], sb_cur[1], sb_cur[2]);
+                mxb = max3(mxb, sb_cur[3], sb_cur[4]);
+                mxb = max3(mxb, sb_cur[5], sb_cur[6]);
+                mxb = max3(mxb, sb_cur[7], sb_cur[8]);
+            } else if constexpr (pc == 3) {
+                mxb = max3(mxb, sb_cur[9], sb_cur[10]);
+                mxb = max3(mxb, sb_cur[11], sb_cur[12]);
+                mxb = max3(mxb, sb_cur[13], sb_cur[14]);
+                mxb = max3(mxb, sb_cur[15], sb_cur[15]);
+            } else if constexpr (pc == 4) {
+                float a2 = mxa, b2 = mxa;
+                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
+                ca = max3(a2, b2, b2) * c;
+                asm volatile("" : "+v"(ca));
+            } else if constexpr (pc == 5) {
+                float a2 = mxb, b2 = mxb;
+                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
+                cb = max3(a2, b2, b2) * c;
+                asm volatile("" : "+v"(cb));
+            } else if constexpr (pc == 6) {
                 const bool grow = (ca > ma + RESCALE_TAU) || (cb > mb + RESCALE_TAU);
                 any = __builtin_amdgcn_ballot_w64(grow) != 0;
-                ma_new = any ? fmaxf(ma, ca) : ma;
-                mb_new = any ? fmaxf(mb, cb) : mb;
+            } else if constexpr (pc == 7) {
+                ma_new = any ? max3(ma, ca, ca) : ma;
+                mb_new = any ? max3(mb, cb, cb) : mb;
+                asm volatile("" : "+v"(ma_new), "+v"(mb_new));
             } else {
-                constexpr int i = u - 4;
-                constexpr int e0 = i * 32 / NEXPU, e1 = (i + 1) * 32 / NEXPU;
-#pragma unroll
-                for (int e = e0; e < e1; ++e) {
-                    if (e < 16)
-                        exp_one(sa_cur, ma_new, psa, pa_out, e);
-                    else
-                        exp_one(sb_cur, mb_new, psb, pb_out, e - 16);
+                constexpr int e = pc - 8, idx = e % 16;
+                f32x16_t& s_ = e < 16 ? sa_cur : sb_cur;
+                const float m_new = e < 16 ? ma_new : mb_new;
+                float& psum = e < 16 ? psa : psb;
+                i32x4_t(&pp)[2] = e < 16 ? pa_out : pb_out;
+                s_[idx] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx], c, -m_new));
+                psum += s_[idx];  // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
+                if constexpr (idx % 2 == 1) {
+                    int w = T::pack2(s_[idx - 1], s_[idx]);
+                    // anchor: keeps this piece in its slot (the optimiser would otherwise sink it
+                    // to the first use of P, after the last MFMA of the stage)
+                    asm volatile("" : "+v"(w), "+v"(psum));
+                    pp[idx >> 3][(idx >> 1) & 3] = w;
+                } else {
+                    asm volatile("" : "+v"(s_[idx]), "+v"(psum));
                 }
             }
         };
-        issue(std::integral_constant<int, 0>{});
-        issue(std::integral_constant<int, 1>{});
-        static_for<0, NU>([&](auto U) {
-            constexpr int u = decltype(U)::value;
-            if constexpr (u + 2 < NU)
-                issue(std::integral_constant<int, u + 2>{});
-            if constexpr (u % 2 == 0) {
-                constexpr int i = u / 2, t = i / DB, db = i % DB;
-                oa[db] = T::mfma(frag[u], pa_in[t], oa[db]);
-                ob[db] = T::mfma(frag[u], pb_in[t], ob[db]);
+        constexpr int PREFETCH = NF >= 8 ? NAUT_PF : 2;  // fragments in flight ahead of the MFMA that consumes them
+        static_for<0, PREFETCH>([&](auto F) { issue(F); });
+        static_for<0, NS>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            constexpr int f = i / 2;
+            if constexpr (i % 2 == 0 && f + PREFETCH < NF)
+                issue(std::integral_constant<int, f + PREFETCH>{});
+            if constexpr (f % 2 == 0) {
+                constexpr int y = f / 2, t = y / DB, db = y % DB;
+                if constexpr (i % 2 == 0)
+                    oa[db] = T::mfma(frag[f], pa_in[t], oa[db]);
+                else
+                    ob[db] = T::mfma(frag[f], pb_in[t], ob[db]);
             } else {
-                constexpr int ks = u / 2;
-                sa_nxt = T::mfma(frag[u], qfa[ks], ks == 0 ? zero16 : sa_nxt);
-                sb_nxt = T::mfma(frag[u], qfb[ks], ks == 0 ? zero16 : sb_nxt);
+                constexpr int ks = f / 2;
+                if constexpr (ks == 0) {
+                    if constexpr (i % 2 == 0)
+                        XM::first(sa_nxt, frag[f], qfa[ks]);
+                    else
+                        XM::first(sb_nxt, frag[f], qfb[ks]);
+                } else {
+                    if constexpr (i % 2 == 0)
+                        XM::acc(sa_nxt, frag[f], qfa[ks]);
+                    else
+                        XM::acc(sb_nxt, frag[f], qfb[ks]);
+                }
             }
-            valu(U);
+            constexpr int p0 = piece_begin<NS>(i), p1 = piece_begin<NS>(i + 1);
+            if constexpr (!(ABL & 1))
+                static_for<p0, p1>([&](auto PC) { piece(PC); });
+            if constexpr ((ABL & 16) != 0) {
+                if (blockIdx.x == 0 && wave == 0 && k >= 40 && k < 44) {
+                    const long long t = __builtin_amdgcn_s_memtime();
+                    if (lane == 0)
+                        ((long long*)(p.lse + (size_t)p.B * p.Hq * S))[(k - 40) * 64 + i] = t;
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
         if (any) {
@@ -718,18 +804,27 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
         la += psa;
         lb += psb;
     };
-    auto needs_mask = [&](int k) { return (CAUSAL && 32 * k + 31 > Q0) || 32 * k + 32 > kv_end_w; };
 
-    // ---- prologue: K tiles 0 and 1, V tile 0; S of block 0 ----
-    load_tile(kg, k_lds, 0, k_grow, k_goff);
-    load_tile(vg, v_lds, 0, v_grow, v_goff);
-    if (ntiles > 1)
-        load_tile(kg, k_lds, 1, k_grow, k_goff);
+    // ---- prologue: the first LA K tiles and LA-1 V tiles ----
+#pragma unroll
+    for (int t = 0; t < LA; ++t)
+        load_tile(kg, k_lds, t, k_goff);
+#pragma unroll
+    for (int t = 0; t + 1 < LA; ++t)
+        load_tile(vg, v_lds, t, v_goff);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    f32x16_t s0a, s0b, s1a, s1b;
-    i32x4_t pea[2], peb[2], poa[2], pob[2];  // P of the last even / odd block
+    // s_e / s_o: scores of the current even / odd block; pe / po: P of the last even / odd block
+    f32x16_t sea, seb, soa, sob;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        sea[r] = 0.f;
+        seb[r] = 0.f;
+        soa[r] = 0.f;
+        sob[r] = 0.f;
+    }
+    i32x4_t pea[2], peb[2], poa[2], pob[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         pea[t] = i32x4_t{0, 0, 0, 0};
@@ -737,20 +832,62 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
         poa[t] = i32x4_t{0, 0, 0, 0};
         pob[t] = i32x4_t{0, 0, 0, 0};
     }
-    stage_x(0, s0a, s0b);
 
+    long long trace_vm = 0, trace_bar = 0, trace_t0 = 0;
+    if constexpr ((ABL & 256) != 0)
+        asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(trace_t0)::"memory");
     for (int j = 0; j < niter; ++j) {
-        if (j + 2 < ntiles)
-            load_tile(kg, k_lds, j + 2, k_grow, k_goff);
-        if (j + 1 < ntiles)
-            load_tile(vg, v_lds, j + 1, v_grow, v_goff);
+        // tiles LA iterations ahead (iteration j reads K tile j and V tile j-1)
+        if constexpr (!(ABL & 8)) {
+            load_tile(kg, k_lds, j + LA, k_goff);
+            load_tile(vg, v_lds, j + LA - 1, v_goff);
+        }
 
-        const int ke = 2 * j, ko = 2 * j + 1;
-        stage(ke, needs_mask(ke), s0a, s0b, s1a, s1b, poa, pob, pea, peb);
-        stage(ko, needs_mask(ko), s1a, s1b, s0a, s0b, pea, peb, poa, pob);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        int k_it[KS], v_it[DB];
+        {
+            const int kbuf = (int)k_lds + (j % NBUF) * TILEB;
+            const int vj = j > 0 ? j - 1 : 0;
+            const int vbuf = (int)v_lds + (vj % NBUF) * TILEB;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                k_it[ks] = k_lane[ks] + kbuf;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+                v_it[db] = v_lane[db] + vbuf;
+        }
+        // stage 2j-1: Y(2j-2) with pe, X(2j) -> s_e, SM(2j-1): s_o -> po
+        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, soa, sob, sea, seb, pea, peb, poa, pob);
+        // stage 2j:   Y(2j-1) with po, X(2j+1) -> s_o, SM(2j): s_e -> pe
+        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, sea, seb, soa, sob, poa, pob, pea, peb);
+
+        // the tiles issued in the previous iteration must have landed; this iteration's may fly on
+        static_assert((LA - 1) * 2 * LD_PER_W < 64, "vmcnt field");
+        long long tr0 = 0, tr1 = 0, tr2 = 0;
+        if constexpr ((ABL & 256) != 0)
+            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tr0)::"memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 1) * 2 * LD_PER_W) : "memory");
+        if constexpr ((ABL & 256) != 0)
+            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tr1)::"memory");
+        if constexpr (!(ABL & 4))
+            __syncthreads();
+        if constexpr ((ABL & 256) != 0) {
+            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tr2)::"memory");
+            trace_vm += tr1 - tr0;
+            trace_bar += tr2 - tr1;
+        }
     }
+    if constexpr ((ABL & 256) != 0) {
+        long long tend;
+        asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tend)::"memory");
+        if (lane == 0) {
+            unsigned long long* dbg = (unsigned long long*)(p.lse + (size_t)p.B * p.Hq * S);
+            atomicAdd(dbg + 0, (unsigned long long)trace_vm);
+            atomicAdd(dbg + 1, (unsigned long long)trace_bar);
+            atomicAdd(dbg + 2, (unsigned long long)(tend - trace_t0));
+            atomicAdd(dbg + 3, 1ull);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue ----
     if (Q0 >= S)
