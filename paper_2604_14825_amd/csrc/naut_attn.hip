@@ -384,13 +384,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
     }
 }
 
-// ---- kernel 2: 64 queries per wavefront, software-pipelined over 32-key blocks -------------
+// ---- kernel 2: software-pipelined over 32-key blocks ------------------------------------------
 //
-// A work-group owns 256 queries (4 wavefronts x 64); each lane owns two queries (one in each
-// 32-query half, "A" and "B").  Every K fragment and every V^T fragment read from LDS feeds two
-// MFMAs (half A and half B), which halves LDS traffic per FLOP compared with 32 queries per
-// wavefront.  With one wavefront per SIMD, matrix and vector work overlap inside the wavefront:
-// the key axis is processed in 32-key blocks and stage k issues
+// A work-group owns 256 queries.  Two shapes share one body:
+//   QH = 1, 8 wavefronts: each wavefront owns 32 queries (each lane one query), two wavefronts per
+//          SIMD, so the hardware can also overlap one wavefront's vector work with the other's MFMAs;
+//   QH = 2, 4 wavefronts: each wavefront owns 64 queries in two 32-query halves, so every K and V^T
+//          fragment read from LDS feeds two MFMAs (half the LDS traffic), one wavefront per SIMD.
+// In both, matrix and vector work overlap inside the wavefront: the key axis is processed in
+// 32-key blocks and stage k issues
 //
 //     MFMA:  Y(k-1) = O^T += V^T . P^T of block k-1      VALU:  SM(k) = online softmax of block k
 //            X(k+1) = S^T of block k+1
@@ -398,20 +400,24 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
 // so the MFMAs of a stage never depend on its vector work.  A stage is laid out as a sequence of
 // slots, one MFMA each, followed by a few vector instructions: the matrix pipe hides about six
 // ordinary vector instructions per MFMA and no more, so the softmax is cut into pieces of that
-// size.  K and V tiles (64 keys) are triple-buffered in LDS and filled by direct global->LDS loads
-// issued two tiles ahead, one barrier per tile.
+// size.  K and V tiles (64 keys) are multi-buffered in LDS and filled by direct global->LDS loads
+// issued LA tiles ahead, one barrier per tile.
 
+#ifndef NAUT_LA
+#define NAUT_LA 3
+#endif
+#ifndef NAUT_PF
+#define NAUT_PF 4
+#endif
 #ifndef NAUT_ABLATE
 #define NAUT_ABLATE 0
 #endif
-constexpr int ABL = NAUT_ABLATE;  // timing experiments only: 1 = no softmax pieces, 2 = no LDS reads, 4 = no barrier, 8 = no tile loads, 16 = trace, 32 = no V^T reads, 64 = no K reads
+constexpr int ABL = NAUT_ABLATE;  // timing experiments only (results are wrong when non-zero): 1 no softmax, 2 no LDS reads, 4 no barrier, 8 no tile loads, 128 tile loads of one address
+#ifndef NAUT_HAO
+#define NAUT_HAO 4
+#endif
+constexpr int HEADS_AT_ONCE = NAUT_HAO;
 constexpr int BM2 = 256;
-#ifndef NAUT_LA
-#define NAUT_LA 2
-#endif
-#ifndef NAUT_PF
-#define NAUT_PF 3
-#endif
 constexpr int LA = NAUT_LA;     // tile loads are issued this many iterations ahead of their use
 constexpr int NBUF = LA + 1;    // LDS buffers per operand
 constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no maximum yet": keeps -inf - (-inf) out
@@ -436,8 +442,8 @@ __device__ __forceinline__ float half_sum(float x)
 // S^T MFMAs written as asm so that their accumulator is an ordinary vector register tuple: the
 // softmax reads every score, and the compiler's own MFMA form would put the scores in the
 // accumulation registers and copy each one out.  Operands never come straight from a vector
-// instruction (A: LDS read, B: resident Q in the accumulation registers, C: an MFMA two slots earlier), and the scores are read
-// a whole stage later, so no software wait states are owed around these.
+// instruction (A: LDS read, B: resident Q in the accumulation registers, C: an earlier MFMA), and
+// the scores are read a whole stage later, so no software wait states are owed around these.
 template <int DT>
 struct XMfma;
 template <>
@@ -450,11 +456,6 @@ struct XMfma<NAUT_BF16> {
     {
         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
     }
-    static __device__ __forceinline__ float dot2acc(int packed, float acc)
-    {
-        const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
-        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, packed), ones, acc, false);
-    }
 };
 template <>
 struct XMfma<NAUT_F16> {
@@ -466,53 +467,73 @@ struct XMfma<NAUT_F16> {
     {
         asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
     }
-    static __device__ __forceinline__ float dot2acc(int packed, float acc)
+};
+
+// The softmax of a stage is cut into pieces: per half two for the in-lane maximum and one for the
+// exchange between lane halves, two for the decision whether the reference maximum moves, then
+// two per score: FE (fma + exp2) and AC (row-sum add, and for odd scores the pack to 16 bit).  FE of
+// score e+1 is placed before AC of score e so that no add waits on the exponential just issued.
+// Approximate issue costs, in 4-cycle vector slots (an exponential counts 2), are dealt out to the
+// MFMA slots greedily, at most `cap` per slot.
+template <int QH>
+struct Pieces {
+    static constexpr int N_MAX = 2 * QH, N_HMAX = QH, N_DEC = 2, NE = 16 * QH, N_ELEM = 2 * NE;
+    static constexpr int HEAD = N_MAX + N_HMAX + N_DEC;
+    static constexpr int N = HEAD + N_ELEM;
+    // element pieces: position -> (is_fe, score index)
+    static constexpr bool is_fe(int pos) { return pos == 0 || (pos != N_ELEM - 1 && pos % 2 == 1); }
+    static constexpr int score(int pos)
     {
-        const f16x2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
-        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, packed), ones, acc, false);
+        return pos == 0 ? 0 : pos == N_ELEM - 1 ? NE - 1 : pos % 2 == 1 ? (pos + 1) / 2 : pos / 2 - 1;
+    }
+    static constexpr int cost(int pc)
+    {
+        if (pc < N_MAX + N_HMAX)
+            return 4;
+        if (pc < HEAD)
+            return pc == N_MAX + N_HMAX ? 4 : 2 + 2 * QH;
+        const int pos = pc - HEAD;
+        return is_fe(pos) ? 3 : (score(pos) % 2 == 1 ? 2 : 1);
+    }
+    template <int NSLOT>
+    static constexpr int begin(int slot)
+    {
+        int total = 0;
+        for (int pc = 0; pc < N; ++pc)
+            total += cost(pc);
+        const int cap = (total + NSLOT - 1) / NSLOT + 1;
+        int pc = 0;
+        for (int s = 0; s < slot && s < NSLOT; ++s) {
+            int used = 0;
+            while (pc < N && (s == NSLOT - 1 || used + cost(pc) <= cap || used == 0)) {
+                used += cost(pc);
+                ++pc;
+            }
+        }
+        return slot >= NSLOT ? N : pc;
     }
 };
 
-// The softmax of a stage is cut into NPIECE pieces (8 for the maxima, one per exponential) whose
-// approximate issue costs, in 4-cycle vector slots (an exponential counts 2), are given here; they
-// are dealt out to the MFMA slots greedily, at most `cap` per slot, in order.
-constexpr int NPIECE = 40;
-constexpr int piece_cost(int pc) { return pc < 6 ? 4 : pc == 6 ? 4 : pc == 7 ? 5 : ((pc - 8) % 2 == 0 ? 4 : 5); }
-template <int NSLOT>
-constexpr int piece_begin(int slot)
-{
-    int total = 0;
-    for (int pc = 0; pc < NPIECE; ++pc)
-        total += piece_cost(pc);
-    const int cap = (total + NSLOT - 1) / NSLOT + 1;
-    int pc = 0;
-    for (int s = 0; s < slot && s < NSLOT; ++s) {
-        int used = 0;
-        // the last slot takes whatever is left
-        while (pc < NPIECE && (s == NSLOT - 1 || used + piece_cost(pc) <= cap || used == 0)) {
-            used += piece_cost(pc);
-            ++pc;
-        }
-    }
-    return slot >= NSLOT ? NPIECE : pc;
-}
-
-template <int D, int DT_IN, int DT_OUT, bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p)
+template <int D, int DT_IN, int DT_OUT, bool CAUSAL, int QH, int NWV>
+__global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p)
 {
     using T = In<DT_IN>;
     using XM = XMfma<DT_IN>;
+    using PC = Pieces<QH>;
+    static_assert(QH * NWV * 32 == BM2, "a work-group owns 256 queries");
     constexpr int ROWB = D * 2;
     constexpr int TILEB = BN * ROWB;           // one 64-key K or V tile
     constexpr int CPR = D / 8;
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
-    constexpr int LD_PER_W = TILEB / 1024 / NWAVES;  // direct loads per wavefront per tile (1 KB each)
+    constexpr int LD_PER_W = TILEB / 1024 / NWV;  // direct loads per wavefront per tile (1 KB each)
     constexpr int NF = 2 * KS;                 // fragments per stage: even = V^T (Y), odd = K (X)
-    constexpr int NS = 2 * NF;                 // slots (MFMAs) per stage
+    constexpr int NS = NF * QH;                // slots (MFMAs) per stage
+    constexpr int WQ = 32 * QH;                // queries per wavefront
     static_assert(2 * DB == KS, "Y and X fragments must pair up");
+    static_assert(LD_PER_W >= 1, "every wavefront must take part in the tile loads");
 
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * TILEB];  // K0 K1 K2 V0 V1 V2
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * TILEB];  // K tiles, then V tiles
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -520,10 +541,27 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
+    // Tile scheduler.  Work-groups are dealt to the 8 XCDs round-robin by block id, and each XCD has
+    // its own L2.  Every XCD is given a contiguous run of (batch, head) pairs and works on
+    // HEADS_AT_ONCE of them at a time, heaviest (last) query tile first, so that the work-groups
+    // resident on an XCD stream few K/V heads through its L2 (query heads that share a K/V head --
+    // grouped-query attention -- sit next to each other).
     const int nbh = p.B * p.Hq;
     const int bid = blockIdx.x;
-    const int qt = p.nqt2 - 1 - bid / nbh;   // heaviest query tiles first
-    const int bh = bid % nbh;
+    int qt, bh;
+    if ((nbh & 7) == 0) {
+        const int xcd = bid & 7, s = bid >> 3;
+        const int hpx = nbh >> 3;                                  // heads per XCD
+        const int G = hpx < HEADS_AT_ONCE ? hpx : HEADS_AT_ONCE;  // heads an XCD works on at a time
+        const int per_group = p.nqt2 * G;
+        const int g = s / per_group, sg = s % per_group;
+        const int ng = hpx - g * G < G ? hpx - g * G : G;          // the last group may be smaller
+        bh = xcd * hpx + g * G + sg % ng;
+        qt = p.nqt2 - 1 - sg / ng;
+    } else {
+        qt = p.nqt2 - 1 - bid / nbh;
+        bh = bid % nbh;
+    }
     const int b = bh / p.Hq;
     const int hq = bh % p.Hq;
     const int hk = hq / (p.Hq / p.Hkv);
@@ -534,28 +572,30 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
     const unsigned char* kg = (const unsigned char*)p.k + (size_t)(b * p.Hkv + hk) * S * ROWB;
     const unsigned char* vg = (const unsigned char*)p.v + (size_t)(b * p.Hkv + hk) * S * ROWB;
 
-    const int Q0 = qt * BM2 + wave * 64;  // first query of this wavefront
-    const int qa = Q0 + l32, qb = Q0 + 32 + l32;
+    const int Q0 = qt * BM2 + wave * WQ;  // first query of this wavefront
+    int qrow[QH];
+#pragma unroll
+    for (int hf = 0; hf < QH; ++hf)
+        qrow[hf] = Q0 + 32 * hf + l32;
 
-    // Q^T fragments of both halves (MFMA B operands), resident for the whole kernel.
-    i32x4_t qfa[KS], qfb[KS];
-    {
-        const int qa_ld = qa < S ? qa : S - 1, qb_ld = qb < S ? qb : S - 1;
+    // Q^T fragments (MFMA B operands), resident in the accumulation registers for the whole kernel.
+    i32x4_t qf[QH][KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            qfa[ks] = *(const i32x4_t*)(qg + (size_t)qa_ld * ROWB + ks * 32 + h * 16);
-            qfb[ks] = *(const i32x4_t*)(qg + (size_t)qb_ld * ROWB + ks * 32 + h * 16);
-        }
+    for (int hf = 0; hf < QH; ++hf) {
+        const int q_ld = qrow[hf] < S ? qrow[hf] : S - 1;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            asm volatile("" : "+a"(qfa[ks]));  // Q lives in the accumulation registers (MFMA B operand)
-            asm volatile("" : "+a"(qfb[ks]));
-        }
+        for (int ks = 0; ks < KS; ++ks)
+            qf[hf][ks] = *(const i32x4_t*)(qg + (size_t)q_ld * ROWB + ks * 32 + h * 16);
     }
+#pragma unroll
+    for (int hf = 0; hf < QH; ++hf)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            asm volatile("" : "+a"(qf[hf][ks]));
 
     // Key range of this wavefront / this work-group (keys at or beyond kv_end_w are dead for it).
     const int kv_end_wg = CAUSAL ? (S < (qt + 1) * BM2 ? S : (qt + 1) * BM2) : S;
-    const int kv_end_w = Q0 >= S ? 0 : (CAUSAL ? (S < Q0 + 64 ? S : Q0 + 64) : S);
+    const int kv_end_w = Q0 >= S ? 0 : (CAUSAL ? (S < Q0 + WQ ? S : Q0 + WQ) : S);
     const int ntiles = (kv_end_wg + BN - 1) / BN;
     const int niter = ntiles + 1;  // stages -1 .. 2*ntiles, two per iteration
 
@@ -589,9 +629,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
         const int rows_left = S - tl * BN;                 // rows of this tile that exist
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i) {
-            int off = goff[i];
-            if constexpr ((ABL & 128) != 0)
-                off = 0;  // timing experiment: every lane reads the same 16 bytes
+            int off = (ABL & 128) ? 0 : goff[i];
             if (rows_left < BN) {  // ragged last tile: re-read the last row instead of running past the end
                 const int row = off / ROWB;
                 off = row < rows_left ? off : (rows_left - 1) * ROWB + off % ROWB;
@@ -621,43 +659,55 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
         }
     }
 
-    f32x16_t oa[DB], ob[DB];
+    f32x16_t oacc[QH][DB];
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int hf = 0; hf < QH; ++hf)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            oa[db][r] = 0.f;
-            ob[db][r] = 0.f;
-        }
-    float ma = M_INIT, mb = M_INIT, la = 0.f, lb = 0.f;
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                oacc[hf][db][r] = 0.f;
+    float m_run[QH], l_run[QH];
+#pragma unroll
+    for (int hf = 0; hf < QH; ++hf) {
+        m_run[hf] = M_INIT;
+        l_run[hf] = 0.f;
+    }
 
     // SM(kblk) part 0: causal / tail / out-of-range masking
-    auto mask_block = [&](int kblk, f32x16_t& sa, f32x16_t& sb) {
+    auto mask_block = [&](int kblk, f32x16_t (&s_)[QH]) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int key = kblk * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
             const bool oob = key >= kv_end_w || kblk < 0;
-            sa[r] = (oob || (CAUSAL && key > qa)) ? -INFINITY : sa[r];
-            sb[r] = (oob || (CAUSAL && key > qb)) ? -INFINITY : sb[r];
+#pragma unroll
+            for (int hf = 0; hf < QH; ++hf)
+                s_[hf][r] = (oob || (CAUSAL && key > qrow[hf])) ? -INFINITY : s_[hf][r];
         }
     };
     auto needs_mask = [&](int k) { return k < 0 || (CAUSAL && 32 * k + 31 > Q0) || 32 * k + 32 > kv_end_w; };
+    // max of three as one instruction (the compiler's fmaxf adds a quieting instruction per operand)
+    auto max3 = [](float x, float y, float z) {
+        float r;
+        asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
+        return r;
+    };
 
     // One pipeline stage k = 2*j - 1 + BLK of iteration j: Y(k-1) reads block BLK of the V tile in
     // v_it, X(k+1) block BLK of the K tile in k_it.  Every wavefront runs every stage: blocks that
     // do not exist for it are fully masked in SM (P = 0, m and l unchanged), Y then adds zeros and
     // X computes scores nobody reads, so one straight-line body serves every k.
-    auto stage = [&](auto BLKC, int k, const int (&k_it)[KS], const int (&v_it)[DB], f32x16_t& sa_cur,
-                     f32x16_t& sb_cur, f32x16_t& sa_nxt, f32x16_t& sb_nxt, const i32x4_t (&pa_in)[2],
-                     const i32x4_t (&pb_in)[2], i32x4_t (&pa_out)[2], i32x4_t (&pb_out)[2]) {
+    auto stage = [&](auto BLKC, int k, const int (&k_it)[KS], const int (&v_it)[DB], f32x16_t (&s_cur)[QH],
+                     f32x16_t (&s_nxt)[QH], const i32x4_t (&p_in)[QH][2], i32x4_t (&p_out)[QH][2]) {
         constexpr int BLK = decltype(BLKC)::value;
         if (needs_mask(k))
-            mask_block(k, sa_cur, sb_cur);
+            mask_block(k, s_cur);
         i32x4_t frag[NF];
         auto issue = [&](auto F) {
             constexpr int f = decltype(F)::value;
-            if constexpr ((ABL & 2) || ((ABL & 32) && f % 2 == 0) || ((ABL & 64) && f % 2 == 1)) {
-                asm volatile("" : "=v"(frag[f]));  // timing experiment: register contents as they are
+            i32x4_t& fr = frag[f];
+            if constexpr ((ABL & 2) != 0) {
+                asm volatile("" : "=v"(fr));
             } else if constexpr (f % 2 == 0) {
                 constexpr int y = f / 2, t = y / DB, db = y % DB;
                 constexpr int off = (BLK * 32 + 16 * t) * ROWB;
@@ -671,138 +721,117 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
                 frag[f] = *(const NAUT_LDS i32x4_t*)(uintptr_t)(k_it[ks] + BLK * 32 * ROWB);
             }
         };
-        float mxa = 0.f, mxb = 0.f, ca = 0.f, cb = 0.f, ma_new = 0.f, mb_new = 0.f, psa = 0.f, psb = 0.f;
+        float mx[QH], cand[QH], m_new[QH], psum[QH];
+#pragma unroll
+        for (int hf = 0; hf < QH; ++hf) {
+            mx[hf] = 0.f;
+            cand[hf] = 0.f;
+            m_new[hf] = 0.f;
+            psum[hf] = 0.f;
+        }
         bool any = false;
-        // max of three as one instruction (the compiler's fmaxf adds a quieting instruction per operand)
-        auto max3 = [](float x, float y, float z) {
-            float r;
-            asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
-            return r;
-        };
-        // vector work of the stage, cut into 8 + 32 pieces (costs in piece_cost)
-        auto piece = [&](auto PC) {
-            constexpr int pc = decltype(PC)::value;
-            if constexpr (pc == 0) {
-                mxa = max3(sa_cur[0], sa_cur[1], sa_cur[2]);
-                mxa = max3(mxa, sa_cur[3], sa_cur[4]);
-                mxa = max3(mxa, sa_cur[5], sa_cur[6]);
-                mxa = max3(mxa, sa_cur[7], sa_cur[8]);
-            } else if constexpr (pc == 1) {
-                mxa = max3(mxa, sa_cur[9], sa_cur[10]);
-                mxa = max3(mxa, sa_cur[11], sa_cur[12]);
-                mxa = max3(mxa, sa_cur[13], sa_cur[14]);
-                mxa = max3(mxa, sa_cur[15], sa_cur[15]);
-            } else if constexpr (pc == 2) {
-                mxb = max3(sb_cur[0], sb_cur[1], sb_cur[2]);
-                mxb = max3(mxb, sb_cur[3], sb_cur[4]);
-                mxb = max3(mxb, sb_cur[5], sb_cur[6]);
-                mxb = max3(mxb, sb_cur[7], sb_cur[8]);
-            } else if constexpr (pc == 3) {
-                mxb = max3(mxb, sb_cur[9], sb_cur[10]);
-                mxb = max3(mxb, sb_cur[11], sb_cur[12]);
-                mxb = max3(mxb, sb_cur[13], sb_cur[14]);
-                mxb = max3(mxb, sb_cur[15], sb_cur[15]);
-            } else if constexpr (pc == 4) {
-                float a2 = mxa, b2 = mxa;
-                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
-                ca = max3(a2, b2, b2) * c;
-                asm volatile("" : "+v"(ca));
-            } else if constexpr (pc == 5) {
-                float a2 = mxb, b2 = mxb;
-                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
-                cb = max3(a2, b2, b2) * c;
-                asm volatile("" : "+v"(cb));
-            } else if constexpr (pc == 6) {
-                const bool grow = (ca > ma + RESCALE_TAU) || (cb > mb + RESCALE_TAU);
-                any = __builtin_amdgcn_ballot_w64(grow) != 0;
-            } else if constexpr (pc == 7) {
-                ma_new = any ? max3(ma, ca, ca) : ma;
-                mb_new = any ? max3(mb, cb, cb) : mb;
-                asm volatile("" : "+v"(ma_new), "+v"(mb_new));
-            } else {
-                constexpr int e = pc - 8, idx = e % 16;
-                f32x16_t& s_ = e < 16 ? sa_cur : sb_cur;
-                const float m_new = e < 16 ? ma_new : mb_new;
-                float& psum = e < 16 ? psa : psb;
-                i32x4_t(&pp)[2] = e < 16 ? pa_out : pb_out;
-                s_[idx] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx], c, -m_new));
-                psum += s_[idx];  // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
-                if constexpr (idx % 2 == 1) {
-                    int w = T::pack2(s_[idx - 1], s_[idx]);
-                    // anchor: keeps this piece in its slot (the optimiser would otherwise sink it
-                    // to the first use of P, after the last MFMA of the stage)
-                    asm volatile("" : "+v"(w), "+v"(psum));
-                    pp[idx >> 3][(idx >> 1) & 3] = w;
+        // vector work of the stage, one piece at a time (see Pieces)
+        auto piece = [&](auto PCI) {
+            constexpr int pc = decltype(PCI)::value;
+            if constexpr (pc < PC::N_MAX) {
+                constexpr int hf = pc / 2;
+                const f32x16_t& s_ = s_cur[hf];
+                if constexpr (pc % 2 == 0) {
+                    mx[hf] = max3(s_[0], s_[1], s_[2]);
+                    mx[hf] = max3(mx[hf], s_[3], s_[4]);
+                    mx[hf] = max3(mx[hf], s_[5], s_[6]);
+                    mx[hf] = max3(mx[hf], s_[7], s_[8]);
                 } else {
-                    asm volatile("" : "+v"(s_[idx]), "+v"(psum));
+                    mx[hf] = max3(mx[hf], s_[9], s_[10]);
+                    mx[hf] = max3(mx[hf], s_[11], s_[12]);
+                    mx[hf] = max3(mx[hf], s_[13], s_[14]);
+                    mx[hf] = max3(mx[hf], s_[15], s_[15]);
+                }
+            } else if constexpr (pc < PC::N_MAX + PC::N_HMAX) {
+                constexpr int hf = pc - PC::N_MAX;
+                float a2 = mx[hf], b2 = mx[hf];
+                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
+                cand[hf] = max3(a2, b2, b2) * c;
+                asm volatile("" : "+v"(cand[hf]));
+            } else if constexpr (pc == PC::N_MAX + PC::N_HMAX) {
+                bool grow = false;
+#pragma unroll
+                for (int hf = 0; hf < QH; ++hf)
+                    grow = grow || (cand[hf] > m_run[hf] + RESCALE_TAU);
+                any = __builtin_amdgcn_ballot_w64(grow) != 0;
+            } else if constexpr (pc == PC::N_MAX + PC::N_HMAX + 1) {
+#pragma unroll
+                for (int hf = 0; hf < QH; ++hf) {
+                    m_new[hf] = any ? max3(m_run[hf], cand[hf], cand[hf]) : m_run[hf];
+                    asm volatile("" : "+v"(m_new[hf]));
+                }
+            } else {
+                constexpr int pos = pc - PC::HEAD, e = PC::score(pos), hf = e / 16, idx = e % 16;
+                f32x16_t& s_ = s_cur[hf];
+                if constexpr (PC::is_fe(pos)) {
+                    s_[idx] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx], c, -m_new[hf]));
+                    // anchor: keeps this piece in its slot (the optimiser would otherwise sink it to
+                    // the first use of P, after the last MFMA of the stage)
+                    asm volatile("" : "+v"(s_[idx]));
+                } else {
+                    psum[hf] += s_[idx];  // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
+                    if constexpr (idx % 2 == 1) {
+                        int w = T::pack2(s_[idx - 1], s_[idx]);
+                        asm volatile("" : "+v"(w), "+v"(psum[hf]));
+                        p_out[hf][idx >> 3][(idx >> 1) & 3] = w;
+                    } else {
+                        asm volatile("" : "+v"(psum[hf]));
+                    }
                 }
             }
         };
-        constexpr int PREFETCH = NF >= 8 ? NAUT_PF : 2;  // fragments in flight ahead of the MFMA that consumes them
+        constexpr int PREFETCH = NAUT_PF < NF ? NAUT_PF : NF - 1;  // fragments in flight ahead of their MFMAs
         static_for<0, PREFETCH>([&](auto F) { issue(F); });
         static_for<0, NS>([&](auto I) {
             constexpr int i = decltype(I)::value;
-            constexpr int f = i / 2;
-            if constexpr (i % 2 == 0 && f + PREFETCH < NF)
+            constexpr int f = i / QH, hf = i % QH;
+            if constexpr (hf == 0 && f + PREFETCH < NF)
                 issue(std::integral_constant<int, f + PREFETCH>{});
             if constexpr (f % 2 == 0) {
                 constexpr int y = f / 2, t = y / DB, db = y % DB;
-                if constexpr (i % 2 == 0)
-                    oa[db] = T::mfma(frag[f], pa_in[t], oa[db]);
-                else
-                    ob[db] = T::mfma(frag[f], pb_in[t], ob[db]);
+                oacc[hf][db] = T::mfma(frag[f], p_in[hf][t], oacc[hf][db]);
             } else {
                 constexpr int ks = f / 2;
-                if constexpr (ks == 0) {
-                    if constexpr (i % 2 == 0)
-                        XM::first(sa_nxt, frag[f], qfa[ks]);
-                    else
-                        XM::first(sb_nxt, frag[f], qfb[ks]);
-                } else {
-                    if constexpr (i % 2 == 0)
-                        XM::acc(sa_nxt, frag[f], qfa[ks]);
-                    else
-                        XM::acc(sb_nxt, frag[f], qfb[ks]);
-                }
+                if constexpr (ks == 0)
+                    XM::first(s_nxt[hf], frag[f], qf[hf][ks]);
+                else
+                    XM::acc(s_nxt[hf], frag[f], qf[hf][ks]);
             }
-            constexpr int p0 = piece_begin<NS>(i), p1 = piece_begin<NS>(i + 1);
+            constexpr int p0 = PC::template begin<NS>(i), p1 = PC::template begin<NS>(i + 1);
             if constexpr (!(ABL & 1))
-                static_for<p0, p1>([&](auto PC) { piece(PC); });
-            if constexpr ((ABL & 16) != 0) {
-                if (blockIdx.x == 0 && wave == 0 && k >= 40 && k < 44) {
-                    const long long t = __builtin_amdgcn_s_memtime();
-                    if (lane == 0)
-                        ((long long*)(p.lse + (size_t)p.B * p.Hq * S))[(k - 40) * 64 + i] = t;
-                }
-            }
+                static_for<p0, p1>([&](auto PCI) { piece(PCI); });
             __builtin_amdgcn_sched_barrier(0);
         });
         if (any) {
-            // repair factors; applied after Y(k-1), whose P was formed against the old maxima
-            const float aa = __builtin_amdgcn_exp2f(ma - ma_new), ab = __builtin_amdgcn_exp2f(mb - mb_new);
-            la *= aa;
-            lb *= ab;
-            // One accumulator block at a time; each block is pinned back into the accumulation
-            // registers right away so that O never lives in ordinary vector registers in the loop.
+            // Repair factors; applied after Y(k-1), whose P was formed against the old maxima.  One
+            // accumulator block at a time, pinned back into the accumulation registers right away so
+            // that O never lives in ordinary vector registers inside the loop.
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
+            for (int hf = 0; hf < QH; ++hf) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run[hf] - m_new[hf]);
+                l_run[hf] *= alpha;
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    oa[db][r] *= aa;
-                asm volatile("" : "+a"(oa[db]));
+                for (int db = 0; db < DB; ++db) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    ob[db][r] *= ab;
-                asm volatile("" : "+a"(ob[db]));
+                    for (int r = 0; r < 16; ++r)
+                        oacc[hf][db][r] *= alpha;
+                    asm volatile("" : "+a"(oacc[hf][db]));
+                }
+                m_run[hf] = m_new[hf];
             }
-            ma = ma_new;
-            mb = mb_new;
         }
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-            asm volatile("" : "+a"(oa[db]), "+a"(ob[db]));
-        la += psa;
-        lb += psb;
+        for (int hf = 0; hf < QH; ++hf) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+                asm volatile("" : "+a"(oacc[hf][db]));
+            l_run[hf] += psum[hf];
+        }
     };
 
     // ---- prologue: the first LA K tiles and LA-1 V tiles ----
@@ -815,27 +844,23 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // s_e / s_o: scores of the current even / odd block; pe / po: P of the last even / odd block
-    f32x16_t sea, seb, soa, sob;
+    // s_e / s_o: scores of the current even / odd block; p_e / p_o: P of the last even / odd block
+    f32x16_t s_e[QH], s_o[QH];
+    i32x4_t p_e[QH][2], p_o[QH][2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        sea[r] = 0.f;
-        seb[r] = 0.f;
-        soa[r] = 0.f;
-        sob[r] = 0.f;
-    }
-    i32x4_t pea[2], peb[2], poa[2], pob[2];
+    for (int hf = 0; hf < QH; ++hf) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        pea[t] = i32x4_t{0, 0, 0, 0};
-        peb[t] = i32x4_t{0, 0, 0, 0};
-        poa[t] = i32x4_t{0, 0, 0, 0};
-        pob[t] = i32x4_t{0, 0, 0, 0};
+        for (int r = 0; r < 16; ++r) {
+            s_e[hf][r] = 0.f;
+            s_o[hf][r] = 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            p_e[hf][t] = i32x4_t{0, 0, 0, 0};
+            p_o[hf][t] = i32x4_t{0, 0, 0, 0};
+        }
     }
 
-    long long trace_vm = 0, trace_bar = 0, trace_t0 = 0;
-    if constexpr ((ABL & 256) != 0)
-        asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(trace_t0)::"memory");
     for (int j = 0; j < niter; ++j) {
         // tiles LA iterations ahead (iteration j reads K tile j and V tile j-1)
         if constexpr (!(ABL & 8)) {
@@ -849,65 +874,50 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
             const int vj = j > 0 ? j - 1 : 0;
             const int vbuf = (int)v_lds + (vj % NBUF) * TILEB;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
+            for (int ks = 0; ks < KS; ++ks) {
                 k_it[ks] = k_lane[ks] + kbuf;
+                asm volatile("" : "+v"(k_it[ks]));  // one add per tile, not one per LDS read
+            }
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db) {
                 v_it[db] = v_lane[db] + vbuf;
+                asm volatile("" : "+v"(v_it[db]));
+            }
         }
-        // stage 2j-1: Y(2j-2) with pe, X(2j) -> s_e, SM(2j-1): s_o -> po
-        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, soa, sob, sea, seb, pea, peb, poa, pob);
-        // stage 2j:   Y(2j-1) with po, X(2j+1) -> s_o, SM(2j): s_e -> pe
-        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, sea, seb, soa, sob, poa, pob, pea, peb);
+        // stage 2j-1: Y(2j-2) with p_e, X(2j) -> s_e, SM(2j-1): s_o -> p_o
+        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, s_o, s_e, p_e, p_o);
+        // stage 2j:   Y(2j-1) with p_o, X(2j+1) -> s_o, SM(2j): s_e -> p_e
+        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, s_e, s_o, p_o, p_e);
 
-        // the tiles issued in the previous iteration must have landed; this iteration's may fly on
+        // the tiles issued LA-1 iterations ago must have landed; newer ones may fly on
         static_assert((LA - 1) * 2 * LD_PER_W < 64, "vmcnt field");
-        long long tr0 = 0, tr1 = 0, tr2 = 0;
-        if constexpr ((ABL & 256) != 0)
-            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tr0)::"memory");
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 1) * 2 * LD_PER_W) : "memory");
-        if constexpr ((ABL & 256) != 0)
-            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tr1)::"memory");
         if constexpr (!(ABL & 4))
             __syncthreads();
-        if constexpr ((ABL & 256) != 0) {
-            asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tr2)::"memory");
-            trace_vm += tr1 - tr0;
-            trace_bar += tr2 - tr1;
-        }
-    }
-    if constexpr ((ABL & 256) != 0) {
-        long long tend;
-        asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(tend)::"memory");
-        if (lane == 0) {
-            unsigned long long* dbg = (unsigned long long*)(p.lse + (size_t)p.B * p.Hq * S);
-            atomicAdd(dbg + 0, (unsigned long long)trace_vm);
-            atomicAdd(dbg + 1, (unsigned long long)trace_bar);
-            atomicAdd(dbg + 2, (unsigned long long)(tend - trace_t0));
-            atomicAdd(dbg + 3, 1ull);
-        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue ----
     if (Q0 >= S)
         return;
-    const float lta = half_sum(la), ltb = half_sum(lb);
     constexpr int OUTB = DT_OUT == NAUT_F32 ? 4 : 2;
-    auto store_half = [&](int q, float m, float lt, const f32x16_t (&o)[DB]) {
+#pragma unroll
+    for (int hf = 0; hf < QH; ++hf) {
+        const int q = qrow[hf];
+        const float lt = half_sum(l_run[hf]);
         if (q >= S)
-            return;
+            continue;
         const float inv_l = 1.0f / lt;
         if (p.lse != nullptr && h == 0)
-            p.lse[(size_t)bh * S + q] = (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
+            p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
         unsigned char* og = (unsigned char*)p.o + ((size_t)bh * S + q) * D * OUTB;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int d = 32 * db + 8 * g + 4 * h;
-                const float x0 = o[db][4 * g + 0] * inv_l, x1 = o[db][4 * g + 1] * inv_l;
-                const float x2 = o[db][4 * g + 2] * inv_l, x3 = o[db][4 * g + 3] * inv_l;
+                const float x0 = oacc[hf][db][4 * g + 0] * inv_l, x1 = oacc[hf][db][4 * g + 1] * inv_l;
+                const float x2 = oacc[hf][db][4 * g + 2] * inv_l, x3 = oacc[hf][db][4 * g + 3] * inv_l;
                 if constexpr (DT_OUT == NAUT_F32) {
                     f32x4_t w = {x0, x1, x2, x3};
                     *(f32x4_t*)(og + d * 4) = w;
@@ -916,9 +926,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void naut_fwd_kernel_v2(const Params p
                     *(i32x2_t*)(og + d * 2) = w;
                 }
             }
-    };
-    store_half(qa, ma, lta, oa);
-    store_half(qb, mb, ltb, ob);
+    }
 }
 
 // ---- host side ---------------------------------------------------------------------
@@ -951,12 +959,21 @@ int launch(const Params& p, int causal, hipStream_t stream)
         return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");
     const dim3 grid((unsigned)nblocks), block(NTHREADS);
     const bool vtr = use_vtr();
-    if (kernel_choice() == 2) {
+    const int kc = kernel_choice();
+    if (kc == 2 || kc == 3) {
         const dim3 grid2((unsigned)((long long)p.nqt2 * p.B * p.Hq));
-        if (causal)
-            hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, true>), grid2, block, 0, stream, p);
-        else
-            hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, false>), grid2, block, 0, stream, p);
+        if (kc == 2) {  // 8 wavefronts x 32 queries
+            const dim3 block2(512);
+            if (causal)
+                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, true, 1, 8>), grid2, block2, 0, stream, p);
+            else
+                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, false, 1, 8>), grid2, block2, 0, stream, p);
+        } else {  // 4 wavefronts x 64 queries
+            if (causal)
+                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, true, 2, 4>), grid2, block, 0, stream, p);
+            else
+                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, false, 2, 4>), grid2, block, 0, stream, p);
+        }
     } else if (causal) {
         if (vtr)
             hipLaunchKernelGGL((naut_fwd_kernel<D, DT_IN, DT_OUT, true, true>), grid, block, 0, stream, p);
