@@ -155,7 +155,7 @@ def main() -> int:
     flops = w.flops
     tflops = flops / (ms_wall * 1e-3) / 1e12
     achieved = flops / (ms_kernel * 1e-3) / 1e12
-    variant = nb.variant_name(w.S, w.D, w.causal, w.in_dtype, w.out_dtype)
+    variant = nb.variant_name(w.B, w.Hq, w.S, w.D, w.causal, w.in_dtype, w.out_dtype)
 
     out = {
         "metric": "attention fwd TFLOP/s (S=16k causal D=128)" if w.name == "long" else "attention fwd TFLOP/s",

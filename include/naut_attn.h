@@ -85,11 +85,15 @@ const char* naut_last_error_string(void);
 int naut_version(void);
 
 /*
- * Name of the kernel variant naut_attn_fwd_dt would launch for these arguments
- * (a static string such as "fwd_d128_bm128_bn64_w4"), or NULL if unsupported.
+ * Name of the kernel variant naut_attn_fwd_dt would launch for these arguments (a static string
+ * such as "fwd_bm256_w8q32_bn64": 256-query work-group tile, 8 wavefronts of 32 queries, 64-key
+ * steps), or NULL if the arguments are unsupported.  The choice of tile shape per workload is the
+ * knob the paper leaves to its auto-tuner (Section 4.4; Section 7.2 reports 64x128 tiles with 4
+ * warps on short sequences against 128x128 with 8); here it is a fixed rule on the number of
+ * work-groups, overridable with the environment variable NAUT_ATTN_VARIANT=w8q32|w4q64|bm128.
  * Host only; used by the benchmark to match profiler rows to launches.
  */
-const char* naut_attn_variant_name(int S, int D, int causal, int in_dtype, int out_dtype);
+const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int in_dtype, int out_dtype);
 
 #ifdef __cplusplus
 }

@@ -54,7 +54,7 @@ def lib():
         L.naut_version.restype = ci
         L.naut_version.argtypes = []
         L.naut_attn_variant_name.restype = ctypes.c_char_p
-        L.naut_attn_variant_name.argtypes = [ci, ci, ci, ci, ci]
+        L.naut_attn_variant_name.argtypes = [ci, ci, ci, ci, ci, ci, ci]
         _lib = L
     return _lib
 
@@ -67,8 +67,8 @@ def version() -> int:
     return int(lib().naut_version())
 
 
-def variant_name(S: int, D: int, causal: bool, in_dtype: int, out_dtype: int):
-    r = lib().naut_attn_variant_name(S, D, int(bool(causal)), in_dtype, out_dtype)
+def variant_name(B: int, Hq: int, S: int, D: int, causal: bool, in_dtype: int, out_dtype: int):
+    r = lib().naut_attn_variant_name(B, Hq, S, D, int(bool(causal)), in_dtype, out_dtype)
     return r.decode() if r is not None else None
 
 

@@ -132,38 +132,23 @@ __device__ __forceinline__ int v_off(int row, int c)
 // 8 values V[key(slot)][d] for the MFMA A operand of the P.V product.
 // The lane owns output row d = 32*db + lane%32 and k-slots 8h..8h+7 (h = lane/32),
 // which stand for keys kbase + 4h + {0..3} and kbase + 8 + 4h + {0..3}.
-template <int D, bool VTR>
+// ds_read_b64_tr_b16: within each 16-lane group, lane i supplies the address of 4 consecutive d of
+// key (i/4) and receives the 4 keys of d = i.
+template <int D>
 __device__ __forceinline__ i32x4_t load_vt_frag(const unsigned char* vt, int kbase, int db, int lane)
 {
     const int h = lane >> 5;
-    if constexpr (VTR) {
-        // ds_read_b64_tr_b16: within each 16-lane group, lane i supplies the address of 4 consecutive
-        // d of key (i/4) and receives the 4 keys of d = i.
-        const int i16 = lane & 15;
-        const int d = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-        const int key = kbase + 4 * h + (i16 >> 2);
-        const int a0 = v_off<D>(key, d >> 3) + (d & 7) * 2;
-        const int a1 = v_off<D>(key + 8, d >> 3) + (d & 7) * 2;
-        i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(vt + a0));
-        i16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(vt + a1));
-        i32x2_t lo = __builtin_bit_cast(i32x2_t, r0);
-        i32x2_t hi = __builtin_bit_cast(i32x2_t, r1);
-        i32x4_t out = {lo.x, lo.y, hi.x, hi.y};
-        return out;
-    } else {
-        const int d = 32 * db + (lane & 31);
-        unsigned short e[8];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int key = kbase + 8 * a + 4 * h + i;
-                e[4 * a + i] = *(const unsigned short*)(vt + v_off<D>(key, d >> 3) + (d & 7) * 2);
-            }
-        i32x4_t out = {(int)(e[0] | ((unsigned)e[1] << 16)), (int)(e[2] | ((unsigned)e[3] << 16)),
-                       (int)(e[4] | ((unsigned)e[5] << 16)), (int)(e[6] | ((unsigned)e[7] << 16))};
-        return out;
-    }
+    const int i16 = lane & 15;
+    const int d = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+    const int key = kbase + 4 * h + (i16 >> 2);
+    const int a0 = v_off<D>(key, d >> 3) + (d & 7) * 2;
+    const int a1 = v_off<D>(key + 8, d >> 3) + (d & 7) * 2;
+    i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(vt + a0));
+    i16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(vt + a1));
+    i32x2_t lo = __builtin_bit_cast(i32x2_t, r0);
+    i32x2_t hi = __builtin_bit_cast(i32x2_t, r1);
+    i32x4_t out = {lo.x, lo.y, hi.x, hi.y};
+    return out;
 }
 
 // max over the two 32-lane halves.  v_permlane32_swap exchanges the upper 32 lanes of its first
@@ -177,10 +162,10 @@ __device__ __forceinline__ float half_max(float x)
     return fmaxf(a, b);
 }
 
-// ---- the kernel ------------------------------------------------------------------
+// ---- kernel 1: 128 queries per work-group, 4 wavefronts x 32 queries, two work-groups per CU ----
 
-template <int D, int DT_IN, int DT_OUT, bool CAUSAL, bool VTR>
-__global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
+template <int D, int DT_IN, int DT_OUT, bool CAUSAL>
+__global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel_bm128(const Params p)
 {
     using T = In<DT_IN>;
     constexpr int ROWB = D * 2;              // bytes per K/V row
@@ -348,7 +333,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
                               T::pack2(sacc[kb][r0 + 4], sacc[kb][r0 + 5]), T::pack2(sacc[kb][r0 + 6], sacc[kb][r0 + 7])};
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const i32x4_t vf = load_vt_frag<D, VTR>(vt, t * 16, db, lane);
+                    const i32x4_t vf = load_vt_frag<D>(vt, t * 16, db, lane);
                     oacc[db] = T::mfma(vf, pb, oacc[db]);
                 }
             }
@@ -414,7 +399,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel(const Params p)
 #endif
 constexpr int ABL = NAUT_ABLATE;  // timing experiments only (results are wrong when non-zero): 1 no softmax, 2 no LDS reads, 4 no barrier, 8 no tile loads, 128 tile loads of one address
 #ifndef NAUT_HAO
-#define NAUT_HAO 4
+#define NAUT_HAO 8
 #endif
 constexpr int HEADS_AT_ONCE = NAUT_HAO;
 constexpr int BM2 = 256;
@@ -939,52 +924,58 @@ int fail(int code, const char* msg)
     return code;
 }
 
-bool use_vtr()
-{
-    const char* e = getenv("NAUT_ATTN_VTR");
-    return e == nullptr || e[0] != '0';
-}
+// Kernel variants (the tile shape / wavefront count / buffering choice the paper leaves to its
+// auto-tuner, Section 4.4 and Section 7.2).  NAUT_ATTN_VARIANT=w8q32|w4q64|bm128 overrides the
+// shape-based choice for A/B runs.
+enum Variant { V_W8Q32 = 0, V_W4Q64 = 1, V_BM128 = 2 };
+const char* const kVariantName[3] = {"fwd_bm256_w8q32_bn64", "fwd_bm256_w4q64_bn64", "fwd_bm128_w4q32_bn64"};
 
-int kernel_choice()
+int pick_variant(int S, long long nbh)
 {
-    const char* e = getenv("NAUT_ATTN_KERNEL");
-    return e == nullptr ? 2 : atoi(e);
+    if (const char* e = getenv("NAUT_ATTN_VARIANT")) {
+        if (!strcmp(e, "w8q32"))
+            return V_W8Q32;
+        if (!strcmp(e, "w4q64"))
+            return V_W4Q64;
+        if (!strcmp(e, "bm128"))
+            return V_BM128;
+    }
+    // 256-query tiles halve the K/V traffic per FLOP; 128-query tiles give twice as many
+    // work-groups, which matters only when there are too few to go round the 256 CUs.
+    const long long wg256 = nbh * ((S + BM2 - 1) / BM2);
+    return wg256 >= 256 ? V_W8Q32 : V_BM128;
 }
 
 template <int D, int DT_IN, int DT_OUT>
 int launch(const Params& p, int causal, hipStream_t stream)
 {
-    const long long nblocks = (long long)p.nqt * p.B * p.Hq;
+    const long long nbh = (long long)p.B * p.Hq;
+    const int variant = pick_variant(p.S, nbh);
+    const long long nblocks = nbh * (variant == V_BM128 ? p.nqt : p.nqt2);
     if (nblocks > 0x7fffffffLL)
         return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");
-    const dim3 grid((unsigned)nblocks), block(NTHREADS);
-    const bool vtr = use_vtr();
-    const int kc = kernel_choice();
-    if (kc == 2 || kc == 3) {
-        const dim3 grid2((unsigned)((long long)p.nqt2 * p.B * p.Hq));
-        if (kc == 2) {  // 8 wavefronts x 32 queries
-            const dim3 block2(512);
-            if (causal)
-                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, true, 1, 8>), grid2, block2, 0, stream, p);
-            else
-                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, false, 1, 8>), grid2, block2, 0, stream, p);
-        } else {  // 4 wavefronts x 64 queries
-            if (causal)
-                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, true, 2, 4>), grid2, block, 0, stream, p);
-            else
-                hipLaunchKernelGGL((naut_fwd_kernel_v2<D, DT_IN, DT_OUT, false, 2, 4>), grid2, block, 0, stream, p);
-        }
-    } else if (causal) {
-        if (vtr)
-            hipLaunchKernelGGL((naut_fwd_kernel<D, DT_IN, DT_OUT, true, true>), grid, block, 0, stream, p);
-        else
-            hipLaunchKernelGGL((naut_fwd_kernel<D, DT_IN, DT_OUT, true, false>), grid, block, 0, stream, p);
+    const dim3 grid((unsigned)nblocks);
+#define NAUT_LAUNCH(KERNEL, THREADS)                                              \
+    do {                                                                          \
+        if (causal)                                                               \
+            hipLaunchKernelGGL((KERNEL<D, DT_IN, DT_OUT, true NAUT_TAIL>), grid, dim3(THREADS), 0, stream, p);  \
+        else                                                                      \
+            hipLaunchKernelGGL((KERNEL<D, DT_IN, DT_OUT, false NAUT_TAIL>), grid, dim3(THREADS), 0, stream, p); \
+    } while (0)
+    if (variant == V_W8Q32) {
+#define NAUT_TAIL , 1, 8
+        NAUT_LAUNCH(naut_fwd_kernel_v2, 512);
+#undef NAUT_TAIL
+    } else if (variant == V_W4Q64) {
+#define NAUT_TAIL , 2, 4
+        NAUT_LAUNCH(naut_fwd_kernel_v2, 256);
+#undef NAUT_TAIL
     } else {
-        if (vtr)
-            hipLaunchKernelGGL((naut_fwd_kernel<D, DT_IN, DT_OUT, false, true>), grid, block, 0, stream, p);
-        else
-            hipLaunchKernelGGL((naut_fwd_kernel<D, DT_IN, DT_OUT, false, false>), grid, block, 0, stream, p);
+#define NAUT_TAIL
+        NAUT_LAUNCH(naut_fwd_kernel_bm128, NTHREADS);
+#undef NAUT_TAIL
     }
+#undef NAUT_LAUNCH
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         snprintf(g_err, sizeof g_err, "kernel launch failed: %s", hipGetErrorString(e));
@@ -1071,13 +1062,12 @@ const char* naut_last_error_string(void) { return g_err; }
 
 int naut_version(void) { return 100; }
 
-const char* naut_attn_variant_name(int S, int D, int causal, int in_dtype, int out_dtype)
+const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int in_dtype, int out_dtype)
 {
-    (void)S;
     (void)causal;
-    if ((D != 64 && D != 128) || !dtype_pair_ok(in_dtype, out_dtype))
+    if (B <= 0 || Hq <= 0 || S <= 0 || (D != 64 && D != 128) || !dtype_pair_ok(in_dtype, out_dtype))
         return nullptr;
-    return D == 128 ? "fwd_d128_bm128_bn64_w4" : "fwd_d64_bm128_bn64_w4";
+    return kVariantName[pick_variant(S, (long long)B * Hq)];
 }
 
 }  // extern "C"

@@ -27,9 +27,9 @@ def test_header_symbols_exported():
 
 def test_version_and_variant_name():
     assert nb.version() >= 100
-    assert nb.variant_name(16384, 128, True, nb.NAUT_BF16, nb.NAUT_BF16)
-    assert nb.variant_name(1024, 64, False, nb.NAUT_F16, nb.NAUT_F32)
-    assert nb.variant_name(1024, 96, False, nb.NAUT_BF16, nb.NAUT_BF16) is None
+    assert nb.variant_name(1, 32, 16384, 128, True, nb.NAUT_BF16, nb.NAUT_BF16) == "fwd_bm256_w8q32_bn64"
+    assert nb.variant_name(1, 2, 256, 64, False, nb.NAUT_F16, nb.NAUT_F32) == "fwd_bm128_w4q32_bn64"
+    assert nb.variant_name(8, 16, 1024, 96, False, nb.NAUT_BF16, nb.NAUT_BF16) is None
 
 
 A = 0x10000  # a fake, 16-byte aligned, never dereferenced device address

@@ -44,6 +44,43 @@ def test_small_shapes_elementwise(B, Hq, Hkv, S, D, causal, idt, odt):
     gu.check(o, lse, o_ref, lse_ref, "small")
 
 
+VARIANT_SHAPES = [
+    (1, 2, 1, 1, 64, True, synth.BF16, synth.BF16),
+    (2, 4, 2, 129, 128, True, synth.BF16, synth.BF16),
+    (1, 2, 2, 257, 128, False, synth.F16, synth.F16),
+    (1, 3, 1, 333, 64, True, synth.F16, synth.F32),
+    (1, 4, 2, 600, 128, True, synth.BF16, synth.BF16),
+    (1, 2, 2, 1024, 64, False, synth.BF16, synth.BF16),
+]
+
+
+@pytest.mark.parametrize("variant", ["w8q32", "w4q64", "bm128"])
+def test_every_kernel_variant(variant, monkeypatch):
+    """Each tile shape / wavefront layout the library can choose gives the same attention."""
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", variant)
+    for B, Hq, Hkv, S, D, causal, idt, odt in VARIANT_SHAPES:
+        seed = 2000 + S + D
+        q = synth.fill(B, Hq, S, D, seed, synth.TAG_Q, idt)
+        k = synth.fill(B, Hkv, S, D, seed, synth.TAG_K, idt, S // 40, 8.0)
+        v = synth.fill(B, Hkv, S, D, seed, synth.TAG_V, idt)
+        scale = 1.0 / math.sqrt(D)
+        print("variant", variant, "case", B, Hq, Hkv, S, D, causal, idt, odt, flush=True)
+        o, lse = gu.run_hip(q, k, v, idt, odt, causal, scale)
+        o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal, scale)
+        gu.check(o, lse, o_ref, lse_ref, variant)
+
+
+@pytest.mark.parametrize("variant", ["w4q64", "bm128"])
+def test_variants_on_prefill_sampled_rows(variant, monkeypatch):
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", variant)
+    w = synth.WORKLOADS["prefill"]
+    q, k, v = synth.make_inputs(w)
+    o, lse = gu.run_hip(q, k, v, w.in_dtype, w.out_dtype, w.causal, w.scale)
+    rows = gu.sample_rows(w, 1024, seed=23, bm=256)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, w.in_dtype, w.causal, w.scale, rows=rows)
+    gu.check(o.reshape(-1, w.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, variant)
+
+
 def test_tiny_workload_full():
     w = synth.WORKLOADS["tiny"]
     q, k, v = synth.make_inputs(w)
