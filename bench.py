@@ -28,7 +28,10 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16/fp16 MFMA: 256 CU x 4096 FLOP/clk
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a plain
 # copy kernel of known size; filled in from profiles/ once measured, else null.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/naut_fwd_bm256_w8q32_long_S16384_D128_causal.md: 740561 KiB x 2.000 read + 133120 KiB x 1.000 written
+    "long": 1.653e9,
+}
 
 PAPER_CONTEXT = ("paper reports relative gains only: up to 23% over state-of-the-art compilers on GH200 and "
                  "up to 42% on RTX 5090 (FP16/FP8, other hardware) -- context, not a target")
@@ -64,23 +67,39 @@ class HipEvents:
         return float(ms.value)
 
 
-def cpu_baseline(w, q, k, v, n_rows: int):
-    """The oracle, as it stands, timed on this machine's host cores on a bounded sample of query rows."""
+def cpu_baseline(w, q, k, v, target_seconds: float):
+    """The oracle, as it stands, timed on this machine's host cores on a bounded sample of query rows.
+
+    A first small batch of rows calibrates the rate; the timed sample is then sized for about
+    `target_seconds` of CPU work (each output row is independent, so a row subset is exact).
+    """
     import numpy as np
     import oracle
-    rows = np.sort(np.random.default_rng(2604).choice(w.B * w.Hq * w.S, size=n_rows, replace=False)).astype(np.int64)
-    t0 = time.perf_counter()
-    oracle.attn_rows(q, k, v, w.in_dtype, w.causal, w.scale, rows=rows)
-    dt = time.perf_counter() - t0
-    keys = (rows % w.S) + 1 if w.causal else np.full(rows.shape, w.S)
-    flops = float((4.0 * w.D * keys).sum())
+    total = w.B * w.Hq * w.S
+    perm = np.random.default_rng(2604).permutation(total)
+
+    def run(rows):
+        rows = np.sort(rows).astype(np.int64)
+        t0 = time.perf_counter()
+        oracle.attn_rows(q, k, v, w.in_dtype, w.causal, w.scale, rows=rows)
+        dt = time.perf_counter() - t0
+        keys = (rows % w.S) + 1 if w.causal else np.full(rows.shape, w.S)
+        return dt, float((4.0 * w.D * keys).sum())
+
+    n0 = min(512, total)
+    dt0, fl0 = run(perm[:n0])
+    # dt0 includes the fixed fp64 decode of K and V; size the real sample from the marginal rate
+    dt_fixed, _ = run(perm[:1])
+    rate = max(dt0 - dt_fixed, 1e-3) / n0
+    n = int(min(total, max(n0, (target_seconds - dt_fixed) / rate)))
+    dt, fl = run(perm[:n])
     return {
-        "value": flops / dt / 1e12,
+        "value": fl / dt / 1e12,
         "unit": "TFLOP/s",
         "cores": int(oracle.threads()),
         "kind": "oracle",
         "sample": "%d of %d query rows (uniform, seeded), %.1f s wall incl. fp64 decode of K,V; same FLOP convention"
-                  % (n_rows, w.B * w.Hq * w.S, dt),
+                  % (n, total, dt),
         "seconds": dt,
     }
 
@@ -88,10 +107,12 @@ def cpu_baseline(w, q, k, v, n_rows: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long")
-    ap.add_argument("--cpu-rows", type=int, default=4096, help="query rows the oracle baseline is timed on (0 = skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="seconds of CPU work the oracle baseline sample is sized for (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=None, help="deprecated spelling: 0 skips the oracle baseline")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB (5 times): the known-size kernel "
                          "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -180,9 +201,8 @@ def main() -> int:
                      "kernel_ms": ms_kernel, "algorithmic_hbm_bytes": w.io_bytes},
         "context": PAPER_CONTEXT,
     }
-    if args.cpu_rows > 0:
-        n = min(args.cpu_rows, w.B * w.Hq * w.S)
-        cb = cpu_baseline(w, q, k, v, n)
+    if args.cpu_seconds > 0 and args.cpu_rows != 0:
+        cb = cpu_baseline(w, q, k, v, args.cpu_seconds)
         cb["gpu_over_cpu"] = tflops / cb["value"]
         out["cpu_baseline"] = cb
     print(json.dumps(out))
