@@ -2,7 +2,7 @@
  * naut_attn.h -- C ABI of the fused attention forward for AMD MI355X (gfx950).
  *
  * The operation is the one the paper's auto-scheduler exists to speed up
- * (Section 1: attention written as "matmuls and softmax"; operator table of
+ * (Section 1: attention given as two matrix products around a softmax; operator table of
  * Section 6: Global, Causal and Grouped-Query attention): for every batch b,
  * query head h and query position i
  *

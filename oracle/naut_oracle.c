@@ -5,9 +5,9 @@
  * check and the benchmark's cpu_baseline leg may load it.  It shares no code,
  * header, table or helper with the HIP path and is never a fallback for it.
  *
- * What it computes: the operator the paper describes as "a sequence of matmuls
- * and softmax" (Section 1, and the operator table in Section 6: Global, Causal
- * and Grouped-Query attention), i.e. for every batch b, query head h, query i
+ * What it computes: the operator the paper takes as its math-level input, two matrix
+ * products with a softmax between them (Section 1, and the operator table in
+ * Section 6: Global, Causal and Grouped-Query attention), i.e. for every batch b, query head h, query i
  *
  *   pass 1 (scores)       s_ij = scale * sum_d q[b,h,i,d] * k[b,hk(h),j,d],   j in J_i
  *   pass 2 (softmax)      m_i = max_j s_ij ; p_ij = exp(s_ij - m_i) ;
