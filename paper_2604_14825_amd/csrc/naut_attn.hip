@@ -515,6 +515,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     constexpr int NF = 2 * KS;                 // fragments per stage: even = V^T (Y), odd = K (X)
     constexpr int NS = NF * QH;                // slots (MFMAs) per stage
     constexpr int WQ = 32 * QH;                // queries per wavefront
+    constexpr int PREFETCH = NAUT_PF < NF ? NAUT_PF : NF - 1;  // LDS fragments in flight ahead of their MFMAs
     static_assert(2 * DB == KS, "Y and X fragments must pair up");
     static_assert(LD_PER_W >= 1, "every wavefront must take part in the tile loads");
 
@@ -678,33 +679,52 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         return r;
     };
 
+    // Fragment f of block BLKX: even f = V^T (two transposed 64-bit reads), odd f = K (one 128-bit
+    // read).  NEXT selects the tiles of the next iteration (same lane addresses plus a scalar delta).
+    auto load_frag = [&](auto F, auto BLKX, auto NEXT, const int (&k_it)[KS], const int (&v_it)[DB], int kdelta,
+                         int vdelta) -> i32x4_t {
+        constexpr int f = decltype(F)::value, BLK = decltype(BLKX)::value;
+        constexpr bool next_iter = decltype(NEXT)::value;
+        if constexpr ((ABL & 2) != 0) {
+            i32x4_t fr;
+            asm volatile("" : "=v"(fr));
+            return fr;
+        } else if constexpr (f % 2 == 0) {
+            constexpr int y = f / 2, t = y / DB, db = y % DB;
+            constexpr int off = (BLK * 32 + 16 * t) * ROWB;
+            const int a = next_iter ? v_it[db] + vdelta : v_it[db];
+            const i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(a + off));
+            const i16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(a + off + 8 * ROWB));
+            const i32x2_t lo = __builtin_bit_cast(i32x2_t, r0), hi = __builtin_bit_cast(i32x2_t, r1);
+            return i32x4_t{lo.x, lo.y, hi.x, hi.y};
+        } else {
+            constexpr int ks = f / 2;
+            const int a = next_iter ? k_it[ks] + kdelta : k_it[ks];
+            return *(const NAUT_LDS i32x4_t*)(uintptr_t)(a + BLK * 32 * ROWB);
+        }
+    };
+
     // One pipeline stage k = 2*j - 1 + BLK of iteration j: Y(k-1) reads block BLK of the V tile in
     // v_it, X(k+1) block BLK of the K tile in k_it.  Every wavefront runs every stage: blocks that
     // do not exist for it are fully masked in SM (P = 0, m and l unchanged), Y then adds zeros and
-    // X computes scores nobody reads, so one straight-line body serves every k.
-    auto stage = [&](auto BLKC, int k, const int (&k_it)[KS], const int (&v_it)[DB], f32x16_t (&s_cur)[QH],
-                     f32x16_t (&s_nxt)[QH], const i32x4_t (&p_in)[QH][2], i32x4_t (&p_out)[QH][2]) {
+    // X computes scores nobody reads, so one straight-line body serves every k.  The first PREFETCH
+    // fragments arrive in `carry` (read during the previous stage) and the last slots read the next
+    // stage's first fragments into it, so no stage starts with an empty LDS pipeline.
+    auto stage = [&](auto BLKC, int k, const int (&k_it)[KS], const int (&v_it)[DB], int kdelta, int vdelta,
+                     i32x4_t (&carry)[PREFETCH], f32x16_t (&s_cur)[QH], f32x16_t (&s_nxt)[QH],
+                     const i32x4_t (&p_in)[QH][2], i32x4_t (&p_out)[QH][2]) {
         constexpr int BLK = decltype(BLKC)::value;
         if (needs_mask(k))
             mask_block(k, s_cur);
         i32x4_t frag[NF];
+        static_for<0, PREFETCH>([&](auto F) { frag[decltype(F)::value] = carry[decltype(F)::value]; });
         auto issue = [&](auto F) {
             constexpr int f = decltype(F)::value;
-            i32x4_t& fr = frag[f];
-            if constexpr ((ABL & 2) != 0) {
-                asm volatile("" : "=v"(fr));
-            } else if constexpr (f % 2 == 0) {
-                constexpr int y = f / 2, t = y / DB, db = y % DB;
-                constexpr int off = (BLK * 32 + 16 * t) * ROWB;
-                const i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(v_it[db] + off));
-                const i16x4_t r1 =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(v_it[db] + off + 8 * ROWB));
-                const i32x2_t lo = __builtin_bit_cast(i32x2_t, r0), hi = __builtin_bit_cast(i32x2_t, r1);
-                frag[f] = i32x4_t{lo.x, lo.y, hi.x, hi.y};
-            } else {
-                constexpr int ks = f / 2;
-                frag[f] = *(const NAUT_LDS i32x4_t*)(uintptr_t)(k_it[ks] + BLK * 32 * ROWB);
-            }
+            if constexpr (f < NF)
+                frag[f] = load_frag(F, std::integral_constant<int, BLK>{}, std::false_type{}, k_it, v_it, 0, 0);
+            else
+                carry[f - NF] = load_frag(std::integral_constant<int, f - NF>{}, std::integral_constant<int, BLK ^ 1>{},
+                                          std::integral_constant<bool, BLK == 1>{}, k_it, v_it, kdelta, vdelta);
         };
         float mx[QH], cand[QH], m_new[QH], psum[QH];
 #pragma unroll
@@ -770,12 +790,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 }
             }
         };
-        constexpr int PREFETCH = NAUT_PF < NF ? NAUT_PF : NF - 1;  // fragments in flight ahead of their MFMAs
-        static_for<0, PREFETCH>([&](auto F) { issue(F); });
         static_for<0, NS>([&](auto I) {
             constexpr int i = decltype(I)::value;
             constexpr int f = i / QH, hf = i % QH;
-            if constexpr (hf == 0 && f + PREFETCH < NF)
+            if constexpr (hf == 0)
                 issue(std::integral_constant<int, f + PREFETCH>{});
             if constexpr (f % 2 == 0) {
                 constexpr int y = f / 2, t = y / DB, db = y % DB;
@@ -846,6 +864,18 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         }
     }
 
+    int k_it[KS], v_it[DB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        k_it[ks] = k_lane[ks] + (int)k_lds;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+        v_it[db] = v_lane[db] + (int)v_lds;
+    i32x4_t carry[PREFETCH];  // first fragments of the coming stage
+    static_for<0, PREFETCH>([&](auto F) {
+        carry[decltype(F)::value] = load_frag(F, std::integral_constant<int, 0>{}, std::false_type{}, k_it, v_it, 0, 0);
+    });
+
     for (int j = 0; j < niter; ++j) {
         // tiles LA iterations ahead (iteration j reads K tile j and V tile j-1)
         if constexpr (!(ABL & 8)) {
@@ -853,30 +883,28 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             load_tile(vg, v_lds, j + LA - 1, v_goff);
         }
 
-        int k_it[KS], v_it[DB];
-        {
-            const int kbuf = (int)k_lds + (j % NBUF) * TILEB;
-            const int vj = j > 0 ? j - 1 : 0;
-            const int vbuf = (int)v_lds + (vj % NBUF) * TILEB;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                k_it[ks] = k_lane[ks] + kbuf;
-                asm volatile("" : "+v"(k_it[ks]));  // one add per tile, not one per LDS read
-            }
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                v_it[db] = v_lane[db] + vbuf;
-                asm volatile("" : "+v"(v_it[db]));
-            }
-        }
+        // LDS addresses of this iteration's tiles; the next iteration's differ by a scalar
+        const int kdelta = (((j + 1) % NBUF) - (j % NBUF)) * TILEB;
+        const int vdelta = ((j % NBUF) - ((j > 0 ? j - 1 : 0) % NBUF)) * TILEB;
         // stage 2j-1: Y(2j-2) with p_e, X(2j) -> s_e, SM(2j-1): s_o -> p_o
-        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, s_o, s_e, p_e, p_o);
+        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, kdelta, vdelta, carry, s_o, s_e, p_e, p_o);
         // stage 2j:   Y(2j-1) with p_o, X(2j+1) -> s_o, SM(2j): s_e -> p_e
-        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, s_e, s_o, p_o, p_e);
+        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, kdelta, vdelta, carry, s_e, s_o, p_o, p_e);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            k_it[ks] += kdelta;
+            asm volatile("" : "+v"(k_it[ks]));  // one add per tile, not one per LDS read
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            v_it[db] += vdelta;
+            asm volatile("" : "+v"(v_it[db]));
+        }
 
-        // the tiles issued LA-1 iterations ago must have landed; newer ones may fly on
-        static_assert((LA - 1) * 2 * LD_PER_W < 64, "vmcnt field");
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 1) * 2 * LD_PER_W) : "memory");
+        // The last slots of the next iteration already read the tiles of the one after it, so the
+        // tiles issued LA-2 iterations ago must have landed by now; newer ones may fly on.
+        static_assert(LA >= 2 && (LA - 2) * 2 * LD_PER_W < 64, "vmcnt field");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
         if constexpr (!(ABL & 4))
             __syncthreads();
     }
