@@ -424,33 +424,39 @@ __device__ __forceinline__ float half_sum(float x)
     return a + b;
 }
 
-// S^T MFMAs written as asm so that their accumulator is an ordinary vector register tuple: the
-// softmax reads every score, and the compiler's own MFMA form would put the scores in the
-// accumulation registers and copy each one out.  Operands never come straight from a vector
-// instruction (A: LDS read, B: resident Q in the accumulation registers, C: an earlier MFMA), and
-// the scores are read a whole stage later, so no software wait states are owed around these.
+// S^T MFMAs of the 64-queries-per-wavefront variant, written as asm so that their accumulator is
+// an ordinary vector register tuple while O and Q live in the accumulation registers (the
+// compiler's own MFMA form would then put the scores there too and copy each one out for the
+// softmax).  The compiler's hazard handling does not look inside asm, so the wait states the
+// hardware does not interlock are owed by hand:
+//   - a vector instruction that writes an MFMA source (the register allocator may route a
+//     fragment through a copy) must be 2 wait states ahead of the MFMA: each asm starts with them;
+//   - an MFMA result may be read by a vector instruction only 11 wait states after the issue of
+//     this 8-pass MFMA: see the guard at the start of `stage`.
+// The 32-queries-per-wavefront variant fits the ordinary vector registers entirely and uses the
+// compiler's MFMA throughout.
 template <int DT>
 struct XMfma;
 template <>
 struct XMfma<NAUT_BF16> {
     static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
     }
     static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
     }
 };
 template <>
 struct XMfma<NAUT_F16> {
     static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
     }
     static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
     }
 };
 
@@ -515,6 +521,13 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     constexpr int NF = 2 * KS;                 // fragments per stage: even = V^T (Y), odd = K (X)
     constexpr int NS = NF * QH;                // slots (MFMAs) per stage
     constexpr int WQ = 32 * QH;                // queries per wavefront
+    constexpr bool ALLV = QH == 1;  // everything fits the ordinary vector registers: no accumulation registers at all
+    auto pin_acc = [](f32x16_t& x) {
+        if constexpr (ALLV)
+            asm volatile("" : "+v"(x));
+        else
+            asm volatile("" : "+a"(x));
+    };
     constexpr int PREFETCH = NAUT_PF < NF ? NAUT_PF : NF - 1;  // LDS fragments in flight ahead of their MFMAs
     static_assert(2 * DB == KS, "Y and X fragments must pair up");
     static_assert(LD_PER_W >= 1, "every wavefront must take part in the tile loads");
@@ -577,7 +590,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     for (int hf = 0; hf < QH; ++hf)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            asm volatile("" : "+a"(qf[hf][ks]));
+            if constexpr (ALLV)
+                asm volatile("" : "+v"(qf[hf][ks]));
+            else
+                asm volatile("" : "+a"(qf[hf][ks]));
 
     // Key range of this wavefront / this work-group (keys at or beyond kv_end_w are dead for it).
     const int kv_end_wg = CAUSAL ? (S < (qt + 1) * BM2 ? S : (qt + 1) * BM2) : S;
@@ -714,17 +730,22 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                      i32x4_t (&carry)[PREFETCH], f32x16_t (&s_cur)[QH], f32x16_t (&s_nxt)[QH],
                      const i32x4_t (&p_in)[QH][2], i32x4_t (&p_out)[QH][2]) {
         constexpr int BLK = decltype(BLKC)::value;
+        // s_cur was written by the asm MFMAs at the end of the previous stage: keep every vector
+        // read of it 11 wait states behind them (see XMfma)
+        if constexpr (!ALLV)
+            asm volatile("s_nop 11" ::: "memory");
         if (needs_mask(k))
             mask_block(k, s_cur);
         i32x4_t frag[NF];
         static_for<0, PREFETCH>([&](auto F) { frag[decltype(F)::value] = carry[decltype(F)::value]; });
         auto issue = [&](auto F) {
             constexpr int f = decltype(F)::value;
-            if constexpr (f < NF)
+            if constexpr (f < NF) {
                 frag[f] = load_frag(F, std::integral_constant<int, BLK>{}, std::false_type{}, k_it, v_it, 0, 0);
-            else
+            } else {
                 carry[f - NF] = load_frag(std::integral_constant<int, f - NF>{}, std::integral_constant<int, BLK ^ 1>{},
                                           std::integral_constant<bool, BLK == 1>{}, k_it, v_it, kdelta, vdelta);
+            }
         };
         float mx[QH], cand[QH], m_new[QH], psum[QH];
 #pragma unroll
@@ -800,7 +821,12 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 oacc[hf][db] = T::mfma(frag[f], p_in[hf][t], oacc[hf][db]);
             } else {
                 constexpr int ks = f / 2;
-                if constexpr (ks == 0)
+                if constexpr (ALLV) {
+                    if constexpr (ks == 0)
+                        s_nxt[hf] = T::mfma(frag[f], qf[hf][ks], f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f});
+                    else
+                        s_nxt[hf] = T::mfma(frag[f], qf[hf][ks], s_nxt[hf]);
+                } else if constexpr (ks == 0)
                     XM::first(s_nxt[hf], frag[f], qf[hf][ks]);
                 else
                     XM::acc(s_nxt[hf], frag[f], qf[hf][ks]);
@@ -823,7 +849,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         oacc[hf][db][r] *= alpha;
-                    asm volatile("" : "+a"(oacc[hf][db]));
+                    pin_acc(oacc[hf][db]);
                 }
                 m_run[hf] = m_new[hf];
             }
@@ -832,7 +858,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         for (int hf = 0; hf < QH; ++hf) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
-                asm volatile("" : "+a"(oacc[hf][db]));
+                pin_acc(oacc[hf][db]);
             l_run[hf] += psum[hf];
         }
     };
