@@ -392,7 +392,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel_bm128(const Param
 #define NAUT_LA 3
 #endif
 #ifndef NAUT_PF
-#define NAUT_PF 4
+#define NAUT_PF 6
+#endif
+#ifndef NAUT_WPAIR
+#define NAUT_WPAIR 1
+#endif
+#ifndef NAUT_SPREAD
+#define NAUT_SPREAD 1
 #endif
 #ifndef NAUT_ABLATE
 #define NAUT_ABLATE 0
@@ -566,6 +572,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     const int hk = hq / (p.Hq / p.Hkv);
     const int S = p.S;
     const float c = p.c;
+    float c_v = c;  // copy held in a vector register: an FMA with a scalar-register operand issues at the slower rate
+    asm volatile("" : "+v"(c_v));
 
     const unsigned char* qg = (const unsigned char*)p.q + (size_t)bh * S * ROWB;
     const unsigned char* kg = (const unsigned char*)p.k + (size_t)(b * p.Hkv + hk) * S * ROWB;
@@ -622,27 +630,41 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         }
     }
     const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
-    // tile index is clamped so that every call issues the same number of loads (the vmcnt
-    // arithmetic below counts on it); a clamped reload lands in a buffer nobody reads.
-    auto load_tile = [&](const unsigned char* g, unsigned lds_tiles, int tile, const int* goff) {
-        const int tl = tile < ntiles ? tile : ntiles - 1;
-        const unsigned dst = lds_tiles + (unsigned)((tile % NBUF) * TILEB + wave * LD_PER_W * 1024);
-        const unsigned char* gt = g + ((ABL & 128) ? (size_t)0 : (size_t)tl * TILEB);  // wave-uniform
-        const int rows_left = S - tl * BN;                 // rows of this tile that exist
+    // Every iteration issues the same number of loads (the vmcnt arithmetic below counts on it):
+    // a tile index past the end is clamped to the last tile, and that reload lands in a buffer
+    // nobody reads.  The last tile may be ragged (S not a multiple of BN): lanes whose row does not
+    // exist re-read the last row that does, through a second set of per-lane offsets.
+    int k_goff_last[LD_PER_W], v_goff_last[LD_PER_W];
+    {
+        const int rows_left = S - (ntiles - 1) * BN;  // >= 1
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i) {
-            int off = (ABL & 128) ? 0 : goff[i];
-            if (rows_left < BN) {  // ragged last tile: re-read the last row instead of running past the end
-                const int row = off / ROWB;
-                off = row < rows_left ? off : (rows_left - 1) * ROWB + off % ROWB;
-            }
-            // asm, so that the compiler does not make every later LDS read wait for these loads;
-            // completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst + i * 1024), "v"(off), "s"(gt)
-                         : "memory", "m0");
+            const int kr = k_goff[i] / ROWB, vr = v_goff[i] / ROWB;
+            k_goff_last[i] = kr < rows_left ? k_goff[i] : (rows_left - 1) * ROWB + k_goff[i] % ROWB;
+            v_goff_last[i] = vr < rows_left ? v_goff[i] : (rows_left - 1) * ROWB + v_goff[i] % ROWB;
         }
+    }
+    struct TileLoad {
+        unsigned dst;             // LDS byte address of this wavefront's part of the tile
+        const unsigned char* gt;  // global address of the tile (wave-uniform)
+        bool last;                // the tile is the last one: use the second set of offsets
+    };
+    auto tile_load = [&](const unsigned char* g, unsigned lds_tiles, int tile) {
+        TileLoad t;
+        const int tl = tile < ntiles ? tile : ntiles - 1;
+        t.dst = lds_tiles + (unsigned)((tile % NBUF) * TILEB + wave * LD_PER_W * 1024);
+        t.gt = g + ((ABL & 128) ? (size_t)0 : (size_t)tl * TILEB);
+        t.last = tile >= ntiles - 1;
+        return t;
+    };
+    // asm, so that the compiler does not make every later LDS read wait for these loads;
+    // completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
+    auto issue_load = [&](const TileLoad& t, int i, const int* goff, const int* goff_last) {
+        const int off = (ABL & 128) ? 0 : (t.last ? goff_last[i] : goff[i]);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(t.dst + i * 1024), "v"(off), "s"(t.gt)
+                     : "memory", "m0");
     };
     const unsigned k_lds = smem_base, v_lds = smem_base + NBUF * TILEB;
 
@@ -687,13 +709,14 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 s_[hf][r] = (oob || (CAUSAL && key > qrow[hf])) ? -INFINITY : s_[hf][r];
         }
     };
-    auto needs_mask = [&](int k) { return k < 0 || (CAUSAL && 32 * k + 31 > Q0) || 32 * k + 32 > kv_end_w; };
-    // max of three as one instruction (the compiler's fmaxf adds a quieting instruction per operand)
-    auto max3 = [](float x, float y, float z) {
-        float r;
-        asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
-        return r;
-    };
+    // first block that needs masking: 32k+31 > Q0 (causal; Q0 is a multiple of 32) or 32k+32 > kv_end_w;
+    // k = -1 (the empty first stage) compares as a huge unsigned number
+    const int kc2 = kv_end_w / 32;
+    const unsigned k_mask_from = (unsigned)(CAUSAL ? (Q0 / 32 < kc2 ? Q0 / 32 : kc2) : kc2);
+    auto needs_mask = [&](int k) { return (unsigned)k >= k_mask_from; };
+    // max of three; the device code is compiled with NaNs assumed absent, so this is one v_max3_f32
+    // with no quieting of the operands
+    auto max3 = [](float x, float y, float z) { return __builtin_fmaxf(__builtin_fmaxf(x, y), z); };
 
     // Fragment f of block BLKX: even f = V^T (two transposed 64-bit reads), odd f = K (one 128-bit
     // read).  NEXT selects the tiles of the next iteration (same lane addresses plus a scalar delta).
@@ -728,7 +751,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     // stage's first fragments into it, so no stage starts with an empty LDS pipeline.
     auto stage = [&](auto BLKC, int k, const int (&k_it)[KS], const int (&v_it)[DB], int kdelta, int vdelta,
                      i32x4_t (&carry)[PREFETCH], f32x16_t (&s_cur)[QH], f32x16_t (&s_nxt)[QH],
-                     const i32x4_t (&p_in)[QH][2], i32x4_t (&p_out)[QH][2]) {
+                     const i32x4_t (&p_in)[QH][2], i32x4_t (&p_out)[QH][2], auto&& side) {
         constexpr int BLK = decltype(BLKC)::value;
         // s_cur was written by the asm MFMAs at the end of the previous stage: keep every vector
         // read of it 11 wait states behind them (see XMfma)
@@ -747,12 +770,13 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                                           std::integral_constant<bool, BLK == 1>{}, k_it, v_it, kdelta, vdelta);
             }
         };
-        float mx[QH], cand[QH], m_new[QH], psum[QH];
+        float mx[QH], cand[QH], m_new[QH], neg_m[QH], psum[QH];
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf) {
             mx[hf] = 0.f;
             cand[hf] = 0.f;
             m_new[hf] = 0.f;
+            neg_m[hf] = 0.f;
             psum[hf] = 0.f;
         }
         bool any = false;
@@ -778,7 +802,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 float a2 = mx[hf], b2 = mx[hf];
                 asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
                 cand[hf] = max3(a2, b2, b2) * c;
-                asm volatile("" : "+v"(cand[hf]));
+                asm volatile("" ::"v"(cand[hf]));
             } else if constexpr (pc == PC::N_MAX + PC::N_HMAX) {
                 bool grow = false;
 #pragma unroll
@@ -789,24 +813,26 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
                 for (int hf = 0; hf < QH; ++hf) {
                     m_new[hf] = any ? max3(m_run[hf], cand[hf], cand[hf]) : m_run[hf];
-                    asm volatile("" : "+v"(m_new[hf]));
+                    neg_m[hf] = -m_new[hf];
+                    asm volatile("" ::"v"(neg_m[hf]));
                 }
             } else {
                 constexpr int pos = pc - PC::HEAD, e = PC::score(pos), hf = e / 16, idx = e % 16;
                 f32x16_t& s_ = s_cur[hf];
                 if constexpr (PC::is_fe(pos)) {
-                    s_[idx] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx], c, -m_new[hf]));
+                    s_[idx] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx], c_v, neg_m[hf]));
                     // anchor: keeps this piece in its slot (the optimiser would otherwise sink it to
-                    // the first use of P, after the last MFMA of the stage)
-                    asm volatile("" : "+v"(s_[idx]));
+                    // the first use of P, after the last MFMA of the stage).  Input-only: an asm that
+                    // also defined the value would make the compiler pad the next use with a wait state.
+                    asm volatile("" ::"v"(s_[idx]));
                 } else {
                     psum[hf] += s_[idx];  // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
                     if constexpr (idx % 2 == 1) {
                         int w = T::pack2(s_[idx - 1], s_[idx]);
-                        asm volatile("" : "+v"(w), "+v"(psum[hf]));
+                        asm volatile("" ::"v"(w), "v"(psum[hf]));
                         p_out[hf][idx >> 3][(idx >> 1) & 3] = w;
                     } else {
-                        asm volatile("" : "+v"(psum[hf]));
+                        asm volatile("" ::"v"(psum[hf]));
                     }
                 }
             }
@@ -816,6 +842,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             constexpr int f = i / QH, hf = i % QH;
             if constexpr (hf == 0)
                 issue(std::integral_constant<int, f + PREFETCH>{});
+            // one wait for two fragments: LDS reads return in order, so waiting here for the next
+            // slot's fragment covers this slot's too and the next slot needs no wait instruction
+            if constexpr (NAUT_WPAIR && hf == 0 && f % 2 == 0 && f + 1 < NF)
+                asm volatile("" ::"v"(frag[f + 1]));
             if constexpr (f % 2 == 0) {
                 constexpr int y = f / 2, t = y / DB, db = y % DB;
                 oacc[hf][db] = T::mfma(frag[f], p_in[hf][t], oacc[hf][db]);
@@ -832,6 +862,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                     XM::acc(s_nxt[hf], frag[f], qf[hf][ks]);
             }
             constexpr int p0 = PC::template begin<NS>(i), p1 = PC::template begin<NS>(i + 1);
+            side(I);
             if constexpr (!(ABL & 1))
                 static_for<p0, p1>([&](auto PCI) { piece(PCI); });
             __builtin_amdgcn_sched_barrier(0);
@@ -866,10 +897,20 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     // ---- prologue: the first LA K tiles and LA-1 V tiles ----
 #pragma unroll
     for (int t = 0; t < LA; ++t)
-        load_tile(kg, k_lds, t, k_goff);
+    {
+        const TileLoad tk = tile_load(kg, k_lds, t);
+#pragma unroll
+        for (int i = 0; i < LD_PER_W; ++i)
+            issue_load(tk, i, k_goff, k_goff_last);
+    }
 #pragma unroll
     for (int t = 0; t + 1 < LA; ++t)
-        load_tile(vg, v_lds, t, v_goff);
+    {
+        const TileLoad tv = tile_load(vg, v_lds, t);
+#pragma unroll
+        for (int i = 0; i < LD_PER_W; ++i)
+            issue_load(tv, i, v_goff, v_goff_last);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -904,18 +945,41 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 
     for (int j = 0; j < niter; ++j) {
         // tiles LA iterations ahead (iteration j reads K tile j and V tile j-1)
-        if constexpr (!(ABL & 8)) {
-            load_tile(kg, k_lds, j + LA, k_goff);
-            load_tile(vg, v_lds, j + LA - 1, v_goff);
+        // The 2*LD_PER_W loads of a wavefront are dealt out over the MFMA slots of one stage (even
+        // wavefronts: the first stage, odd ones: the second) rather than issued in one burst by all
+        // wavefronts right after the barrier, which backs up the memory pipeline and stalls them.
+        const TileLoad kt = tile_load(kg, k_lds, j + LA), vt = tile_load(vg, v_lds, j + LA - 1);
+        if constexpr (!(ABL & 8) && NAUT_SPREAD == 0) {
+#pragma unroll
+            for (int i = 0; i < LD_PER_W; ++i)
+                issue_load(kt, i, k_goff, k_goff_last);
+#pragma unroll
+            for (int i = 0; i < LD_PER_W; ++i)
+                issue_load(vt, i, v_goff, v_goff_last);
         }
+        auto side = [&](auto BLKC, auto I) {
+            constexpr int BLK = decltype(BLKC)::value, i = decltype(I)::value;
+            constexpr int NL = 2 * LD_PER_W, STEP = NS / NL;
+            if constexpr (!(ABL & 8) && NAUT_SPREAD != 0 && STEP > 0 && i % STEP == STEP / 2 && i / STEP < NL) {
+                constexpr int q = i / STEP;
+                if (NAUT_SPREAD == 1 ? BLK == 0 : (wave & 1) == BLK) {
+                    if constexpr (q < LD_PER_W)
+                        issue_load(kt, q, k_goff, k_goff_last);
+                    else
+                        issue_load(vt, q - LD_PER_W, v_goff, v_goff_last);
+                }
+            }
+        };
 
         // LDS addresses of this iteration's tiles; the next iteration's differ by a scalar
         const int kdelta = (((j + 1) % NBUF) - (j % NBUF)) * TILEB;
         const int vdelta = ((j % NBUF) - ((j > 0 ? j - 1 : 0) % NBUF)) * TILEB;
         // stage 2j-1: Y(2j-2) with p_e, X(2j) -> s_e, SM(2j-1): s_o -> p_o
-        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, kdelta, vdelta, carry, s_o, s_e, p_e, p_o);
+        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, kdelta, vdelta, carry, s_o, s_e, p_e, p_o,
+              [&](auto I) { side(std::integral_constant<int, 0>{}, I); });
         // stage 2j:   Y(2j-1) with p_o, X(2j+1) -> s_o, SM(2j): s_e -> p_e
-        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, kdelta, vdelta, carry, s_e, s_o, p_o, p_e);
+        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, kdelta, vdelta, carry, s_e, s_o, p_o, p_e,
+              [&](auto I) { side(std::integral_constant<int, 1>{}, I); });
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             k_it[ks] += kdelta;
