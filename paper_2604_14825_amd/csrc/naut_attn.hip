@@ -55,6 +55,7 @@ constexpr int BN = 64;   // keys per step
 constexpr int NWAVES = 4;
 constexpr int NTHREADS = NWAVES * 64;
 constexpr float RESCALE_TAU = 6.0f;  // log2 units
+constexpr float P_LIMIT = 1024.0f;   // a block's per-lane row sum above this moves the reference maximum
 
 struct Params {
     const void* q;
@@ -466,32 +467,20 @@ struct XMfma<NAUT_F16> {
     }
 };
 
-// The softmax of a stage is cut into pieces: per half two for the in-lane maximum and one for the
-// exchange between lane halves, two for the decision whether the reference maximum moves, then
-// two per score: FE (fma + exp2) and AC (row-sum add, and for odd scores the pack to 16 bit).  FE of
-// score e+1 is placed before AC of score e so that no add waits on the exponential just issued.
-// Approximate issue costs, in 4-cycle vector slots (an exponential counts 2), are dealt out to the
-// MFMA slots greedily, at most `cap` per slot.
+// The softmax of a stage is cut into two pieces per score: FE (fma + exp2) and AC (row-sum add, and
+// for odd scores the pack to 16 bit).  FE of score e+1 is placed before AC of score e so that no
+// add waits on the exponential just issued.  Approximate issue costs, in vector slots (an
+// exponential counts 2), are dealt out to the MFMA slots greedily, at most `cap` per slot.
 template <int QH>
 struct Pieces {
-    static constexpr int N_MAX = 2 * QH, N_HMAX = QH, N_DEC = 2, NE = 16 * QH, N_ELEM = 2 * NE;
-    static constexpr int HEAD = N_MAX + N_HMAX + N_DEC;
-    static constexpr int N = HEAD + N_ELEM;
-    // element pieces: position -> (is_fe, score index)
-    static constexpr bool is_fe(int pos) { return pos == 0 || (pos != N_ELEM - 1 && pos % 2 == 1); }
+    static constexpr int NE = 16 * QH, N = 2 * NE;
+    // position -> (is_fe, score index)
+    static constexpr bool is_fe(int pos) { return pos == 0 || (pos != N - 1 && pos % 2 == 1); }
     static constexpr int score(int pos)
     {
-        return pos == 0 ? 0 : pos == N_ELEM - 1 ? NE - 1 : pos % 2 == 1 ? (pos + 1) / 2 : pos / 2 - 1;
+        return pos == 0 ? 0 : pos == N - 1 ? NE - 1 : pos % 2 == 1 ? (pos + 1) / 2 : pos / 2 - 1;
     }
-    static constexpr int cost(int pc)
-    {
-        if (pc < N_MAX + N_HMAX)
-            return 4;
-        if (pc < HEAD)
-            return pc == N_MAX + N_HMAX ? 4 : 2 + 2 * QH;
-        const int pos = pc - HEAD;
-        return is_fe(pos) ? 3 : (score(pos) % 2 == 1 ? 2 : 1);
-    }
+    static constexpr int cost(int pos) { return is_fe(pos) ? 3 : (score(pos) % 2 == 1 ? 2 : 1); }
     template <int NSLOT>
     static constexpr int begin(int slot)
     {
@@ -659,8 +648,20 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     };
     // asm, so that the compiler does not make every later LDS read wait for these loads;
     // completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
+    i32x4_t sink[4];  // ablation 64 only: tile loads land in these dedicated registers instead of LDS
+    if constexpr ((ABL & 64) != 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sink[i] = i32x4_t{0, 0, 0, 0};
+            asm volatile("" : "+v"(sink[i]));
+        }
+    }
     auto issue_load = [&](const TileLoad& t, int i, const int* goff, const int* goff_last) {
         const int off = (ABL & 128) ? 0 : (t.last ? goff_last[i] : goff[i]);
+        if constexpr ((ABL & 64) != 0) {
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(sink[i & 3]) : "v"(off), "s"(t.gt) : "memory");
+            return;
+        }
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
                      : "s"(t.dst + i * 1024), "v"(off), "s"(t.gt)
@@ -691,10 +692,11 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 oacc[hf][db][r] = 0.f;
-    float m_run[QH], l_run[QH];
+    float m_run[QH], neg_m[QH], l_run[QH];  // reference maximum (log2 units), its negation, running sum
 #pragma unroll
     for (int hf = 0; hf < QH; ++hf) {
         m_run[hf] = M_INIT;
+        neg_m[hf] = -M_INIT;
         l_run[hf] = 0.f;
     }
 
@@ -728,6 +730,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             i32x4_t fr;
             asm volatile("" : "=v"(fr));
             return fr;
+        } else if constexpr (f % 2 == 0 && (ABL & 32) != 0) {  // timing only: V^T fragment as one plain 128-bit read
+            constexpr int y = f / 2, t = y / DB, db = y % DB;
+            const int a = next_iter ? k_it[db + 4 * t] + kdelta : k_it[db + 4 * t];
+            return *(const NAUT_LDS i32x4_t*)(uintptr_t)(a + BLK * 32 * ROWB + NBUF * TILEB);
         } else if constexpr (f % 2 == 0) {
             constexpr int y = f / 2, t = y / DB, db = y % DB;
             constexpr int off = (BLK * 32 + 16 * t) * ROWB;
@@ -770,70 +776,29 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                                           std::integral_constant<bool, BLK == 1>{}, k_it, v_it, kdelta, vdelta);
             }
         };
-        float mx[QH], cand[QH], m_new[QH], neg_m[QH], psum[QH];
+        float psum[QH], pe[QH][16];  // this block's row sums (per lane: its 16 of the 32 keys) and exponentials
 #pragma unroll
-        for (int hf = 0; hf < QH; ++hf) {
-            mx[hf] = 0.f;
-            cand[hf] = 0.f;
-            m_new[hf] = 0.f;
-            neg_m[hf] = 0.f;
+        for (int hf = 0; hf < QH; ++hf)
             psum[hf] = 0.f;
-        }
-        bool any = false;
-        // vector work of the stage, one piece at a time (see Pieces)
+        // Vector work of the stage, one piece at a time (see Pieces).  P is formed against the
+        // reference maximum as it stands, with no look at this block's own maximum: as long as the
+        // row sums stay below P_LIMIT every P is below it too, and the reference need not move.
         auto piece = [&](auto PCI) {
-            constexpr int pc = decltype(PCI)::value;
-            if constexpr (pc < PC::N_MAX) {
-                constexpr int hf = pc / 2;
-                const f32x16_t& s_ = s_cur[hf];
-                if constexpr (pc % 2 == 0) {
-                    mx[hf] = max3(s_[0], s_[1], s_[2]);
-                    mx[hf] = max3(mx[hf], s_[3], s_[4]);
-                    mx[hf] = max3(mx[hf], s_[5], s_[6]);
-                    mx[hf] = max3(mx[hf], s_[7], s_[8]);
-                } else {
-                    mx[hf] = max3(mx[hf], s_[9], s_[10]);
-                    mx[hf] = max3(mx[hf], s_[11], s_[12]);
-                    mx[hf] = max3(mx[hf], s_[13], s_[14]);
-                    mx[hf] = max3(mx[hf], s_[15], s_[15]);
-                }
-            } else if constexpr (pc < PC::N_MAX + PC::N_HMAX) {
-                constexpr int hf = pc - PC::N_MAX;
-                float a2 = mx[hf], b2 = mx[hf];
-                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
-                cand[hf] = max3(a2, b2, b2) * c;
-                asm volatile("" ::"v"(cand[hf]));
-            } else if constexpr (pc == PC::N_MAX + PC::N_HMAX) {
-                bool grow = false;
-#pragma unroll
-                for (int hf = 0; hf < QH; ++hf)
-                    grow = grow || (cand[hf] > m_run[hf] + RESCALE_TAU);
-                any = __builtin_amdgcn_ballot_w64(grow) != 0;
-            } else if constexpr (pc == PC::N_MAX + PC::N_HMAX + 1) {
-#pragma unroll
-                for (int hf = 0; hf < QH; ++hf) {
-                    m_new[hf] = any ? max3(m_run[hf], cand[hf], cand[hf]) : m_run[hf];
-                    neg_m[hf] = -m_new[hf];
-                    asm volatile("" ::"v"(neg_m[hf]));
-                }
+            constexpr int pos = decltype(PCI)::value, e = PC::score(pos), hf = e / 16, idx = e % 16;
+            if constexpr (PC::is_fe(pos)) {
+                pe[hf][idx] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[hf][idx], c_v, neg_m[hf]));
+                // anchor: keeps this piece in its slot (the optimiser would otherwise sink it to the
+                // first use of P, after the last MFMA of the stage).  Input-only: an asm that also
+                // defined the value would make the compiler pad the next use with a wait state.
+                asm volatile("" ::"v"(pe[hf][idx]));
             } else {
-                constexpr int pos = pc - PC::HEAD, e = PC::score(pos), hf = e / 16, idx = e % 16;
-                f32x16_t& s_ = s_cur[hf];
-                if constexpr (PC::is_fe(pos)) {
-                    s_[idx] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx], c_v, neg_m[hf]));
-                    // anchor: keeps this piece in its slot (the optimiser would otherwise sink it to
-                    // the first use of P, after the last MFMA of the stage).  Input-only: an asm that
-                    // also defined the value would make the compiler pad the next use with a wait state.
-                    asm volatile("" ::"v"(s_[idx]));
+                psum[hf] += pe[hf][idx];  // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
+                if constexpr (idx % 2 == 1) {
+                    int w = T::pack2(pe[hf][idx - 1], pe[hf][idx]);
+                    asm volatile("" ::"v"(w), "v"(psum[hf]));
+                    p_out[hf][idx >> 3][(idx >> 1) & 3] = w;
                 } else {
-                    psum[hf] += s_[idx];  // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
-                    if constexpr (idx % 2 == 1) {
-                        int w = T::pack2(s_[idx - 1], s_[idx]);
-                        asm volatile("" ::"v"(w), "v"(psum[hf]));
-                        p_out[hf][idx >> 3][(idx >> 1) & 3] = w;
-                    } else {
-                        asm volatile("" ::"v"(psum[hf]));
-                    }
+                    asm volatile("" ::"v"(psum[hf]));
                 }
             }
         };
@@ -842,20 +807,17 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             constexpr int f = i / QH, hf = i % QH;
             if constexpr (hf == 0)
                 issue(std::integral_constant<int, f + PREFETCH>{});
-            // one wait for two fragments: LDS reads return in order, so waiting here for the next
-            // slot's fragment covers this slot's too and the next slot needs no wait instruction
-            if constexpr (NAUT_WPAIR && hf == 0 && f % 2 == 0 && f + 1 < NF)
-                asm volatile("" ::"v"(frag[f + 1]));
+            const i32x4_t& fr_op = (ABL & 16) ? qf[0][0] : frag[f];  // ablation 16: the reads feed nothing
             if constexpr (f % 2 == 0) {
                 constexpr int y = f / 2, t = y / DB, db = y % DB;
-                oacc[hf][db] = T::mfma(frag[f], p_in[hf][t], oacc[hf][db]);
+                oacc[hf][db] = T::mfma(fr_op, p_in[hf][t], oacc[hf][db]);
             } else {
                 constexpr int ks = f / 2;
                 if constexpr (ALLV) {
                     if constexpr (ks == 0)
-                        s_nxt[hf] = T::mfma(frag[f], qf[hf][ks], f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f});
+                        s_nxt[hf] = T::mfma(fr_op, qf[hf][ks], f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f});
                     else
-                        s_nxt[hf] = T::mfma(frag[f], qf[hf][ks], s_nxt[hf]);
+                        s_nxt[hf] = T::mfma(fr_op, qf[hf][ks], s_nxt[hf]);
                 } else if constexpr (ks == 0)
                     XM::first(s_nxt[hf], frag[f], qf[hf][ks]);
                 else
@@ -865,15 +827,43 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             side(I);
             if constexpr (!(ABL & 1))
                 static_for<p0, p1>([&](auto PCI) { piece(PCI); });
+            // one wait for two fragments: LDS reads return in order, so waiting at the end of an odd
+            // slot for the fragment two slots on covers the next slot's too, and neither of the two
+            // coming slots needs a wait instruction of its own
+            if constexpr (NAUT_WPAIR && hf == QH - 1 && f % 2 == 1 && f + 2 < NF)
+                asm volatile("" ::"v"(frag[f + 2]));
             __builtin_amdgcn_sched_barrier(0);
         });
-        if (any) {
-            // Repair factors; applied after Y(k-1), whose P was formed against the old maxima.  One
-            // accumulator block at a time, pinned back into the accumulation registers right away so
-            // that O never lives in ordinary vector registers inside the loop.
+        if constexpr ((ABL & 16) != 0) {
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+                asm volatile("" ::"v"(frag[f]));
+        }
+        bool over = false;  // also true for +inf (first block of a row: the reference is still M_INIT)
+#pragma unroll
+        for (int hf = 0; hf < QH; ++hf)
+            over = over || psum[hf] > P_LIMIT;
+        if (__builtin_amdgcn_ballot_w64(over) != 0) {
+            // Rare path: some row of this wavefront met scores far above its reference maximum.  Move
+            // the reference of every row to its true running maximum, apply the repair factor
+            // exp2(m_old - m_new) to l and O (after Y(k-1), whose P was formed against the old
+            // maxima), and form this block's P again from the scores, which are still intact.
 #pragma unroll
             for (int hf = 0; hf < QH; ++hf) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run[hf] - m_new[hf]);
+                const f32x16_t& s_ = s_cur[hf];
+                float mx = max3(s_[0], s_[1], s_[2]);
+                mx = max3(mx, s_[3], s_[4]);
+                mx = max3(mx, s_[5], s_[6]);
+                mx = max3(mx, s_[7], s_[8]);
+                mx = max3(mx, s_[9], s_[10]);
+                mx = max3(mx, s_[11], s_[12]);
+                mx = max3(mx, s_[13], s_[14]);
+                mx = max3(mx, s_[15], s_[15]);
+                float a2 = mx, b2 = mx;
+                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
+                const float cand = max3(a2, b2, b2) * c;  // -inf if the block is masked for this row
+                const float m_new = max3(m_run[hf], cand, cand);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[hf] - m_new);
                 l_run[hf] *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
@@ -882,7 +872,17 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                         oacc[hf][db][r] *= alpha;
                     pin_acc(oacc[hf][db]);
                 }
-                m_run[hf] = m_new[hf];
+                m_run[hf] = m_new;
+                neg_m[hf] = -m_new;
+                float ps = 0.f;
+#pragma unroll
+                for (int idx = 0; idx < 16; idx += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx], c_v, neg_m[hf]));
+                    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[idx + 1], c_v, neg_m[hf]));
+                    ps += p0 + p1;
+                    p_out[hf][idx >> 3][(idx >> 1) & 3] = T::pack2(p0, p1);
+                }
+                psum[hf] = ps;
             }
         }
 #pragma unroll
@@ -994,11 +994,22 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // The last slots of the next iteration already read the tiles of the one after it, so the
         // tiles issued LA-2 iterations ago must have landed by now; newer ones may fly on.
         static_assert(LA >= 2 && (LA - 2) * 2 * LD_PER_W < 64, "vmcnt field");
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
+        if constexpr (!(ABL & 256))  // ablation 256 (timing only): tiles are read without waiting for them
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
+        // A bare barrier, not __syncthreads(): the fence in the latter would first drain the LDS
+        // reads in flight, which are this wavefront's prefetch for the next stage.  They target
+        // tiles published by the previous barrier and buffers that no load overwrites before the
+        // barrier after this one, so they may stay in flight; the tile loads to be published have
+        // been awaited just above.
         if constexpr (!(ABL & 4))
-            __syncthreads();
+            asm volatile("s_barrier" ::: "memory");
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr ((ABL & 64) != 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            asm volatile("" ::"v"(sink[i]));
+    }
 
     // ---- epilogue ----
     if (Q0 >= S)
