@@ -90,7 +90,9 @@ int naut_version(void);
  * steps), or NULL if the arguments are unsupported.  The choice of tile shape per workload is the
  * knob the paper leaves to its auto-tuner (Section 4.4; Section 7.2 reports 64x128 tiles with 4
  * warps on short sequences against 128x128 with 8); here it is a fixed rule on the number of
- * work-groups, overridable with the environment variable NAUT_ATTN_VARIANT=w8q32|w4q64|bm128.
+ * work-groups and the length of the key loop, fitted to timings of every variant over a grid of
+ * shapes (python -m paper_2604_14825_amd.tune prints that table and flags where the rule loses), and
+ * overridable with the environment variable NAUT_ATTN_VARIANT=w8q32|w4q64|bm128.
  * Host only; used by the benchmark to match profiler rows to launches.
  */
 const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int in_dtype, int out_dtype);

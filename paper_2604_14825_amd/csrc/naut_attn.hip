@@ -509,7 +509,6 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     static_assert(QH * NWV * 32 == BM2, "a work-group owns 256 queries");
     constexpr int ROWB = D * 2;
     constexpr int TILEB = BN * ROWB;           // one 64-key K or V tile
-    constexpr int CPR = D / 8;
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
     constexpr int LD_PER_W = TILEB / 1024 / NWV;  // direct loads per wavefront per tile (1 KB each)
@@ -1059,7 +1058,7 @@ int fail(int code, const char* msg)
 enum Variant { V_W8Q32 = 0, V_W4Q64 = 1, V_BM128 = 2 };
 const char* const kVariantName[3] = {"fwd_bm256_w8q32_bn64", "fwd_bm256_w4q64_bn64", "fwd_bm128_w4q32_bn64"};
 
-int pick_variant(int S, long long nbh)
+int pick_variant(int S, long long nbh, int D, int causal)
 {
     if (const char* e = getenv("NAUT_ATTN_VARIANT")) {
         if (!strcmp(e, "w8q32"))
@@ -1069,17 +1068,22 @@ int pick_variant(int S, long long nbh)
         if (!strcmp(e, "bm128"))
             return V_BM128;
     }
-    // 256-query tiles halve the K/V traffic per FLOP; 128-query tiles give twice as many
-    // work-groups, which matters only when there are too few to go round the 256 CUs.
+    // Rule fitted to the timings of `python -m paper_2604_14825_amd.tune` over sequence lengths
+    // 256..16384, 2..512 heads, both head dimensions, with and without the causal mask.  The
+    // pipelined 256-query kernel halves the K/V traffic per FLOP but pays a fill and a drain stage
+    // per work-group and needs a full wave of work-groups: it wins once there is one work-group per
+    // CU and the key loop is long enough (average keys per query times D above 2^16).  The
+    // 64-queries-per-wavefront variant was never the fastest and is selectable by name only.
     const long long wg256 = nbh * ((S + BM2 - 1) / BM2);
-    return wg256 >= 256 ? V_W8Q32 : V_BM128;
+    const long long loop_work = (long long)(causal ? (S + 1) / 2 : S) * D;
+    return (wg256 >= 256 && loop_work > 65536) ? V_W8Q32 : V_BM128;
 }
 
 template <int D, int DT_IN, int DT_OUT>
 int launch(const Params& p, int causal, hipStream_t stream)
 {
     const long long nbh = (long long)p.B * p.Hq;
-    const int variant = pick_variant(p.S, nbh);
+    const int variant = pick_variant(p.S, nbh, D, causal);
     const long long nblocks = nbh * (variant == V_BM128 ? p.nqt : p.nqt2);
     if (nblocks > 0x7fffffffLL)
         return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");
@@ -1193,10 +1197,9 @@ int naut_version(void) { return 100; }
 
 const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int in_dtype, int out_dtype)
 {
-    (void)causal;
     if (B <= 0 || Hq <= 0 || S <= 0 || (D != 64 && D != 128) || !dtype_pair_ok(in_dtype, out_dtype))
         return nullptr;
-    return kVariantName[pick_variant(S, (long long)B * Hq)];
+    return kVariantName[pick_variant(S, (long long)B * Hq, D, causal)];
 }
 
 }  // extern "C"

@@ -32,6 +32,24 @@ def test_version_and_variant_name():
     assert nb.variant_name(8, 16, 1024, 96, False, nb.NAUT_BF16, nb.NAUT_BF16) is None
 
 
+def test_variant_rule_and_override(monkeypatch):
+    """The fixed selection rule on the five benchmark shapes and on a short causal one; the override."""
+    monkeypatch.delenv("NAUT_ATTN_VARIANT", raising=False)
+    bf = nb.NAUT_BF16
+    big, small = "fwd_bm256_w8q32_bn64", "fwd_bm128_w4q32_bn64"
+    assert nb.variant_name(1, 2, 256, 64, False, nb.NAUT_F16, nb.NAUT_F32) == small      # tiny
+    assert nb.variant_name(8, 16, 1024, 64, False, bf, bf) == small                      # encoder: short key loop
+    assert nb.variant_name(4, 32, 4096, 128, True, bf, bf) == big                        # prefill
+    assert nb.variant_name(2, 64, 8192, 128, True, bf, bf) == big                        # grouped-query
+    assert nb.variant_name(1, 32, 16384, 128, True, bf, bf) == big                       # long
+    assert nb.variant_name(1, 512, 512, 128, True, bf, bf) == small                      # many heads, short causal loop
+    assert nb.variant_name(1, 8, 4096, 128, False, bf, bf) == small                      # too few work-groups for 256 CUs
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", "w4q64")
+    assert nb.variant_name(1, 2, 256, 64, False, bf, bf) == "fwd_bm256_w4q64_bn64"
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", "nonsense")
+    assert nb.variant_name(1, 32, 16384, 128, True, bf, bf) == big
+
+
 A = 0x10000  # a fake, 16-byte aligned, never dereferenced device address
 
 

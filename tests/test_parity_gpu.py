@@ -44,6 +44,50 @@ def test_small_shapes_elementwise(B, Hq, Hkv, S, D, causal, idt, odt):
     gu.check(o, lse, o_ref, lse_ref, "small")
 
 
+def _bits_to_f32(bits, dtype):
+    if dtype == synth.F16:
+        return bits.view(np.float16).astype(np.float32)
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def _key_profile(kind, S):
+    """Per-key multipliers that drive the running maximum the hard way."""
+    j = np.arange(S, dtype=np.float32)
+    if kind == "ascending":      # later keys ever larger: the reference maximum moves again and again
+        return 0.25 + 12.0 * j / max(S - 1, 1)
+    if kind == "descending":     # the first block holds the maximum: the reference never moves after it
+        return 12.25 - 12.0 * j / max(S - 1, 1)
+    if kind == "late_spike":     # one key, late in the sequence, dwarfs everything before it
+        f = np.ones(S, dtype=np.float32)
+        f[(3 * S) // 4] = 60.0
+        return f
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("variant", ["w8q32", "w4q64", "bm128"])
+@pytest.mark.parametrize("kind", ["ascending", "descending", "late_spike"])
+def test_moving_reference_maximum(kind, variant, monkeypatch):
+    """Score profiles that exercise the repair path of the online softmax: a maximum that keeps growing,
+    one that is met in the first block, and a single late key far above the rest (near one-hot rows)."""
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", variant)
+    B, Hq, Hkv, S, D, causal, idt, odt = 1, 4, 2, 700, 128, True, synth.BF16, synth.F32
+    seed = 4242
+    q = synth.fill(B, Hq, S, D, seed, synth.TAG_Q, idt)
+    k = synth.fill(B, Hkv, S, D, seed, synth.TAG_K, idt)
+    v = synth.fill(B, Hkv, S, D, seed, synth.TAG_V, idt)
+    kf = _bits_to_f32(k, idt) * _key_profile(kind, S)[None, None, :, None]
+    k = synth.round16(kf, idt)
+    scale = 1.0 / math.sqrt(D)
+    print("case", kind, variant, flush=True)
+    o, lse = gu.run_hip(q, k, v, idt, odt, causal, scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal, scale)
+    gu.check(o, lse, o_ref, lse_ref, kind + "/" + variant)
+    for causal2 in (False,):
+        o, lse = gu.run_hip(q, k, v, idt, odt, causal2, 4.0 * scale)  # hotter softmax: scores in the hundreds
+        o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal2, 4.0 * scale)
+        gu.check(o, lse, o_ref, lse_ref, kind + "/" + variant + "/hot")
+
+
 VARIANT_SHAPES = [
     (1, 2, 1, 1, 64, True, synth.BF16, synth.BF16),
     (2, 4, 2, 129, 128, True, synth.BF16, synth.BF16),
