@@ -47,6 +47,11 @@ def _bind(path: str):
     lib.naut_oracle_attn_rows.restype = ctypes.c_int
     lib.naut_oracle_attn_rows.argtypes = ([u16p, u16p, u16p, ctypes.c_int, i64p, ctypes.c_int64, dp, dp]
                                           + [ctypes.c_int] * 6 + [ctypes.c_double])
+    lib.naut_oracle_attn_cross_f64.restype = ctypes.c_int
+    lib.naut_oracle_attn_cross_f64.argtypes = [dp, dp, dp, dp, dp] + [ctypes.c_int] * 7 + [ctypes.c_double]
+    lib.naut_oracle_attn_cross16.restype = ctypes.c_int
+    lib.naut_oracle_attn_cross16.argtypes = ([u16p, u16p, u16p, ctypes.c_int, dp, dp] + [ctypes.c_int] * 7
+                                             + [ctypes.c_double])
     lib.naut_oracle_decode16.restype = ctypes.c_int
     lib.naut_oracle_decode16.argtypes = [u16p, ctypes.c_int, dp, ctypes.c_int64]
     lib.naut_oracle_threads.restype = ctypes.c_int
@@ -118,6 +123,40 @@ def attn_rows(q_bits, k_bits, v_bits, in_dtype: int, causal: bool, scale: float,
         raise RuntimeError("naut_oracle_attn_rows failed: %d" % rc)
     if rows is None:
         return o.reshape(B, Hq, S, D), lse.reshape(B, Hq, S)
+    return o, lse
+
+
+def attn_cross_f64(q, k, v, causal: bool, scale: float):
+    """Decode-time attention on fp64 arrays: q [B,Hq,Sq,D] (the last Sq positions), k,v [B,Hkv,Sk,D] -> (o, lse)."""
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    k = np.ascontiguousarray(k, dtype=np.float64)
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    assert k.shape == (B, Hkv, Sk, D) and v.shape == k.shape
+    o = np.empty((B, Hq, Sq, D), dtype=np.float64)
+    lse = np.empty((B, Hq, Sq), dtype=np.float64)
+    rc = _load().naut_oracle_attn_cross_f64(_dptr(q), _dptr(k), _dptr(v), _dptr(o), _dptr(lse), B, Hq, Hkv, Sq, Sk,
+                                            D, int(bool(causal)), float(scale))
+    if rc != 0:
+        raise RuntimeError("naut_oracle_attn_cross_f64 failed: %d" % rc)
+    return o, lse
+
+
+def attn_cross16(q_bits, k_bits, v_bits, in_dtype: int, causal: bool, scale: float):
+    """The same on 16-bit patterns (uint16 arrays shaped like q/k/v)."""
+    q = np.ascontiguousarray(q_bits, dtype=np.uint16)
+    k = np.ascontiguousarray(k_bits, dtype=np.uint16)
+    v = np.ascontiguousarray(v_bits, dtype=np.uint16)
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    assert k.shape == (B, Hkv, Sk, D) and v.shape == k.shape
+    o = np.empty((B, Hq, Sq, D), dtype=np.float64)
+    lse = np.empty((B, Hq, Sq), dtype=np.float64)
+    rc = _load().naut_oracle_attn_cross16(_u16ptr(q), _u16ptr(k), _u16ptr(v), int(in_dtype), _dptr(o), _dptr(lse),
+                                          B, Hq, Hkv, Sq, Sk, D, int(bool(causal)), float(scale))
+    if rc != 0:
+        raise RuntimeError("naut_oracle_attn_cross16 failed: %d" % rc)
     return o, lse
 
 

@@ -242,6 +242,85 @@ int naut_oracle_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *
     return err;
 }
 
+/* ---- decode-time attention: Sq queries against Sk keys -------------------- */
+
+/*
+ * The paper's second workload (Section 6: "DC", a few new query positions against a long key/value
+ * cache).  q,o [B][Hq][Sq][D]; k,v [B][Hkv][Sk][D]; lse [B][Hq][Sq] (may be NULL).  The Sq queries
+ * are the LAST Sq positions of a sequence of Sk, so with `causal` query i sees keys
+ * J_i = {0 .. Sk-Sq+i} (the diagonal is kept; Sk >= Sq is then required), and without it all Sk
+ * keys.  Same three passes per row as above; Sq == Sk gives exactly the self-attention entry points.
+ * Pinned (tests/test_oracle_pins.py) by: equality with the self-attention entry at Sq == Sk, equality
+ * with the last Sq rows of a causal self-attention over Sk, the prefix property, a hand-expanded case,
+ * V = 1 and Q = 0 closed forms.
+ * Returns 0, -1 on bad arguments, -2 if memory cannot be had.
+ */
+int naut_oracle_attn_cross_f64(const double *q, const double *k, const double *v, double *o, double *lse,
+                               int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, double scale)
+{
+    if (!q || !k || !v || !o || bad_shape(B, Hq, Hkv, Sq, D) || Sk <= 0 || (causal && Sk < Sq))
+        return -1;
+    const int g = Hq / Hkv;
+    const int64_t nrows = (int64_t)B * Hq * Sq;
+    int err = 0;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)Sk);
+        if (!s) {
+#pragma omp atomic write
+            err = -2;
+        }
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t r = 0; r < nrows; ++r) {
+            if (!s)
+                continue;
+            const int64_t i = r % Sq;
+            const int64_t h = (r / Sq) % Hq;
+            const int64_t b = r / ((int64_t)Sq * Hq);
+            const int64_t hk = h / g;
+            const int64_t nkeys = causal ? (int64_t)Sk - Sq + i + 1 : Sk;
+            const double *Kh = k + (b * Hkv + hk) * (int64_t)Sk * D;
+            const double *Vh = v + (b * Hkv + hk) * (int64_t)Sk * D;
+            double lse_r;
+            attn_row(q + r * D, Kh, Vh, nkeys, D, scale, s, o + r * D, &lse_r);
+            if (lse)
+                lse[r] = lse_r;
+        }
+        free(s);
+    }
+    return err;
+}
+
+/* The same on bf16/fp16 bit patterns, decoded exactly. */
+int naut_oracle_attn_cross16(const uint16_t *q, const uint16_t *k, const uint16_t *v, int in_dtype, double *o,
+                             double *lse, int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal,
+                             double scale)
+{
+    if (!q || !k || !v || !o || bad_shape(B, Hq, Hkv, Sq, D) || Sk <= 0 || (causal && Sk < Sq))
+        return -1;
+    if (in_dtype != NAUT_ORACLE_BF16 && in_dtype != NAUT_ORACLE_F16)
+        return -1;
+    const int64_t nq = (int64_t)B * Hq * Sq * D, nkv = (int64_t)B * Hkv * Sk * D;
+    double *Q64 = (double *)malloc(sizeof(double) * (size_t)nq);
+    double *K64 = (double *)malloc(sizeof(double) * (size_t)nkv);
+    double *V64 = (double *)malloc(sizeof(double) * (size_t)nkv);
+    int rc = -2;
+    if (Q64 && K64 && V64) {
+        for (int64_t t = 0; t < nq; ++t)
+            Q64[t] = decode16(q[t], in_dtype);
+#pragma omp parallel for schedule(static)
+        for (int64_t t = 0; t < nkv; ++t) {
+            K64[t] = decode16(k[t], in_dtype);
+            V64[t] = decode16(v[t], in_dtype);
+        }
+        rc = naut_oracle_attn_cross_f64(Q64, K64, V64, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale);
+    }
+    free(Q64);
+    free(K64);
+    free(V64);
+    return rc;
+}
+
 /* Exact decode of n 16-bit patterns to fp64 (exposed so tests can pin the decoders). */
 int naut_oracle_decode16(const uint16_t *bits, int dtype, double *out, int64_t n)
 {

@@ -26,6 +26,12 @@ MUTANTS = {
     "f16_bias": ("expo - 15)", "expo - 16)"),
     "bf16_shift": ("(uint32_t)bits << 16", "(uint32_t)bits << 15"),
     "batch_stride": ("const int64_t b = r / ((int64_t)S * Hq);", "const int64_t b = 0;"),
+    # decode-time entry points (Sq queries against Sk keys)
+    "cross_causal_top_left_aligned": ("causal ? (int64_t)Sk - Sq + i + 1 : Sk", "causal ? i + 1 : Sk"),
+    "cross_causal_drops_diagonal": ("causal ? (int64_t)Sk - Sq + i + 1 : Sk", "causal ? (int64_t)Sk - Sq + i + (i > 0 || Sk > Sq ? 0 : 1) : Sk"),
+    "cross_kv_head_stride_uses_Sq": ("const double *Kh = k + (b * Hkv + hk) * (int64_t)Sk * D;", "const double *Kh = k + (b * Hkv + hk) * (int64_t)Sq * D;"),
+    "cross_row_split_uses_Sk": ("const int64_t h = (r / Sq) % Hq;", "const int64_t h = (r / Sk) % Hq;"),
+    "cross16_decodes_V_from_K": ("V64[t] = decode16(v[t], in_dtype);\n        }\n        rc =", "V64[t] = decode16(k[t], in_dtype);\n        }\n        rc ="),
 }
 
 
@@ -51,6 +57,15 @@ def run_pins():
     pins.test_one_hot_limit()
     pins.test_large_scores_do_not_overflow()
     pins.test_decoders_exact_all_patterns()
+    for causal in (False, True):
+        pins.test_cross_equals_self_attention_when_Sq_is_Sk(causal)
+    for sq in (1, 3, 8):
+        pins.test_cross_causal_is_the_tail_of_causal_self_attention(sq)
+    pins.test_cross_noncausal_is_global_attention_with_padded_queries()
+    pins.test_cross_hand_expanded_Sq2_Sk3_causal()
+    pins.test_cross_closed_forms_and_gqa()
+    for dt in (oracle.BF16, oracle.F16):
+        pins.test_cross16_matches_f64_entry(dt)
 
 
 def test_unmutated_copy_passes(tmp_path, monkeypatch):

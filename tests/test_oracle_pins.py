@@ -328,3 +328,99 @@ def test_bad_arguments_rejected():
     k = np.zeros((1, 2, 4, 2))
     with pytest.raises(RuntimeError):
         oracle.attn_f64(q, k, k, False, 1.0)          # Hq % Hkv != 0
+
+
+# ---------------------------------------------------------------------------
+# decode-time attention (Section 6 of the paper, workload "DC"): Sq queries, the last positions of
+# a sequence of Sk, against all Sk keys
+# ---------------------------------------------------------------------------
+
+def rand_cross(seed, B, Hq, Hkv, Sq, Sk, D):
+    g = rng(seed)
+    return (g.standard_normal((B, Hq, Sq, D)), g.standard_normal((B, Hkv, Sk, D)),
+            g.standard_normal((B, Hkv, Sk, D)))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_cross_equals_self_attention_when_Sq_is_Sk(causal):
+    q, k, v = rand_qkv(31, 2, 4, 2, 13, 8)
+    o1, l1 = oracle.attn_f64(q, k, v, causal, 0.3)
+    o2, l2 = oracle.attn_cross_f64(q, k, v, causal, 0.3)
+    np.testing.assert_array_equal(o1, o2)
+    np.testing.assert_array_equal(l1, l2)
+
+
+@pytest.mark.parametrize("Sq", [1, 3, 8])
+def test_cross_causal_is_the_tail_of_causal_self_attention(Sq):
+    # the last Sq rows of a causal self-attention over Sk positions, computed from those queries alone
+    Sk = 17
+    q, k, v = rand_qkv(32, 2, 6, 3, Sk, 4)
+    o_full, l_full = oracle.attn_f64(q, k, v, True, 0.7)
+    o, lse = oracle.attn_cross_f64(q[:, :, Sk - Sq:], k, v, True, 0.7)
+    np.testing.assert_allclose(o, o_full[:, :, Sk - Sq:], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(lse, l_full[:, :, Sk - Sq:], rtol=0, atol=1e-15)
+
+
+def test_cross_noncausal_is_global_attention_with_padded_queries():
+    # without the mask every query sees all keys: same as a global self-attention whose first Sq
+    # queries are ours (the other query rows are irrelevant to ours)
+    Sq, Sk = 3, 11
+    q, k, v = rand_cross(33, 1, 4, 2, Sq, Sk, 8)
+    qpad = np.concatenate([q, rng(1).standard_normal((1, 4, Sk - Sq, 8))], axis=2)
+    o_full, l_full = oracle.attn_f64(qpad, k, v, False, 0.25)
+    o, lse = oracle.attn_cross_f64(q, k, v, False, 0.25)
+    np.testing.assert_allclose(o, o_full[:, :, :Sq], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(lse, l_full[:, :, :Sq], rtol=0, atol=1e-15)
+
+
+def test_cross_hand_expanded_Sq2_Sk3_causal():
+    # query 0 is position 1 (sees keys 0,1), query 1 is position 2 (sees keys 0,1,2); D = 1
+    q = np.array([[[[2.0], [-1.0]]]])
+    k = np.array([[[[0.5], [1.0], [-2.0]]]])
+    v = np.array([[[[1.0], [10.0], [100.0]]]])
+    sc = 0.5
+    o, lse = oracle.attn_cross_f64(q, k, v, True, sc)
+    e00, e01 = math.exp(sc * 2.0 * 0.5), math.exp(sc * 2.0 * 1.0)
+    assert abs(o[0, 0, 0, 0] - (e00 * 1.0 + e01 * 10.0) / (e00 + e01)) < 1e-14
+    assert abs(lse[0, 0, 0] - math.log(e00 + e01)) < 1e-14
+    f0, f1, f2 = math.exp(sc * -1.0 * 0.5), math.exp(sc * -1.0 * 1.0), math.exp(sc * -1.0 * -2.0)
+    assert abs(o[0, 0, 1, 0] - (f0 * 1.0 + f1 * 10.0 + f2 * 100.0) / (f0 + f1 + f2)) < 1e-13
+    assert abs(lse[0, 0, 1] - math.log(f0 + f1 + f2)) < 1e-14
+
+
+def test_cross_closed_forms_and_gqa():
+    Sq, Sk = 4, 9
+    q, k, v = rand_cross(34, 2, 6, 2, Sq, Sk, 8)
+    o, _ = oracle.attn_cross_f64(q, k, np.ones_like(v), True, 0.4)
+    np.testing.assert_allclose(o, 1.0, rtol=0, atol=1e-14)
+    o, lse = oracle.attn_cross_f64(np.zeros_like(q), k, v, True, 0.4)
+    for i in range(Sq):
+        n = Sk - Sq + i + 1
+        np.testing.assert_allclose(lse[:, :, i], math.log(n), rtol=0, atol=1e-14)
+        np.testing.assert_allclose(o[:, :, i], np.repeat(v[:, :, :n].mean(axis=2), 3, axis=1), rtol=0, atol=1e-14)
+    # grouped-query == multi-head with each K/V head repeated for its group of consecutive query heads
+    o1, l1 = oracle.attn_cross_f64(q, k, v, True, 0.4)
+    o2, l2 = oracle.attn_cross_f64(q, np.repeat(k, 3, axis=1), np.repeat(v, 3, axis=1), True, 0.4)
+    np.testing.assert_array_equal(o1, o2)
+    np.testing.assert_array_equal(l1, l2)
+
+
+@pytest.mark.parametrize("dtype", [oracle.BF16, oracle.F16])
+def test_cross16_matches_f64_entry(dtype):
+    g = rng(35)
+    Sq, Sk = 2, 40
+    bits = lambda shape: (g.integers(0, 1 << 15, shape).astype(np.uint16) & (0x3FFF if dtype == oracle.F16 else 0x3FFF)) \
+        | (g.integers(0, 2, shape).astype(np.uint16) << 15)
+    q, k, v = bits((1, 4, Sq, 8)), bits((1, 2, Sk, 8)), bits((1, 2, Sk, 8))
+    o1, l1 = oracle.attn_cross16(q, k, v, dtype, True, 0.35)
+    o2, l2 = oracle.attn_cross_f64(oracle.decode16(q, dtype), oracle.decode16(k, dtype), oracle.decode16(v, dtype),
+                                   True, 0.35)
+    np.testing.assert_array_equal(o1, o2)
+    np.testing.assert_array_equal(l1, l2)
+
+
+def test_cross_bad_arguments_rejected():
+    q, k, v = rand_cross(36, 1, 2, 2, 5, 3, 4)
+    with pytest.raises(RuntimeError):
+        oracle.attn_cross_f64(q, k, v, True, 1.0)   # causal needs Sk >= Sq
+    oracle.attn_cross_f64(q, k, v, False, 1.0)      # fine without the mask
