@@ -37,6 +37,8 @@
 #ifndef NAUT_ATTN_H
 #define NAUT_ATTN_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -96,6 +98,33 @@ int naut_version(void);
  * Host only; used by the benchmark to match profiler rows to launches.
  */
 const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int in_dtype, int out_dtype);
+
+/*
+ * Decode-time attention (the paper's second workload, "DC", Section 6: decoding with a key/value
+ * cache): Sq new query positions per head, taken to be the LAST Sq positions of a sequence of Sk,
+ * attend to all Sk cached keys.  Same operator as above with
+ *     q, o : [B][Hq][Sq][D]     k, v : [B][Hkv][Sk][D]     lse : [B][Hq][Sq] (fp32, may be NULL)
+ * and J_i = {0..Sk-1}, or {0..Sk-Sq+i} when `causal` is non-zero (then Sk >= Sq is required; Sq == Sk
+ * gives the causal self-attention of naut_attn_fwd).  bf16 in and out.  The work is bound by reading
+ * K and V once, so the key axis is split over work-groups and the partial results are merged by the
+ * split-merge identity of softmax (the rolling update of Section 4.2/4.3 applied across splits
+ * instead of across steps); the partials live in `workspace`, DEVICE memory owned by the caller, 16-byte
+ * aligned, of at least naut_attn_decode_workspace_bytes(...) bytes, which the call overwrites and
+ * which must not be shared by calls that may overlap.  Two kernels are enqueued on `stream`; nothing
+ * is allocated, nothing is synchronised.  Errors as above (a missing or short workspace is
+ * NAUT_ERR_SHAPE).
+ */
+int naut_attn_decode(const void* q, const void* k, const void* v, void* o, float* lse,
+                     int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same with explicit storage types (see naut_attn_fwd_dt). */
+int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, float* lse,
+                        int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
+                        void* workspace, size_t workspace_bytes, void* stream, int in_dtype, int out_dtype);
+
+/* Bytes of workspace naut_attn_decode[_dt] needs for these sizes; 0 if they are unsupported.  Host only. */
+size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D);
 
 #ifdef __cplusplus
 }

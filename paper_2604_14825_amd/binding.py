@@ -24,7 +24,7 @@ NAUT_F16 = 1
 NAUT_F32 = 2
 
 EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
-           "naut_attn_variant_name")
+           "naut_attn_variant_name", "naut_attn_decode", "naut_attn_decode_dt", "naut_attn_decode_workspace_bytes")
 
 _lib = None
 
@@ -55,6 +55,13 @@ def lib():
         L.naut_version.argtypes = []
         L.naut_attn_variant_name.restype = ctypes.c_char_p
         L.naut_attn_variant_name.argtypes = [ci, ci, ci, ci, ci, ci, ci]
+        sz = ctypes.c_size_t
+        L.naut_attn_decode.restype = ci
+        L.naut_attn_decode.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
+        L.naut_attn_decode_dt.restype = ci
+        L.naut_attn_decode_dt.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci]
+        L.naut_attn_decode_workspace_bytes.restype = sz
+        L.naut_attn_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
         _lib = L
     return _lib
 
@@ -118,5 +125,56 @@ def naut_attn_fwd(q, k, v, o, lse, causal: bool, scale: float, stream=None):
     else:
         rc = naut_attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, S, D,
                                causal, scale, stream.cuda_stream, in_dt, out_dt)
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())
+
+
+def decode_workspace_bytes(B: int, Hq: int, Hkv: int, Sq: int, Sk: int, D: int) -> int:
+    """Bytes of device workspace naut_attn_decode needs for these sizes (0: unsupported)."""
+    return int(lib().naut_attn_decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D))
+
+
+def naut_attn_decode_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale, ws_ptr, ws_bytes,
+                         stream_ptr, in_dtype=None, out_dtype=None) -> int:
+    """Direct call with integer device addresses; returns the status code."""
+    L = lib()
+    if in_dtype is None and out_dtype is None:
+        return int(L.naut_attn_decode(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, int(causal),
+                                      float(scale), ws_ptr, ws_bytes, stream_ptr))
+    return int(L.naut_attn_decode_dt(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, int(causal),
+                                     float(scale), ws_ptr, ws_bytes, stream_ptr, int(in_dtype), int(out_dtype)))
+
+
+def naut_attn_decode(q, k, v, o, lse, causal: bool, scale: float, workspace, stream=None):
+    """Decode-time attention on torch device tensors (used for memory and streams only).
+
+    q,o [B,Hq,Sq,D] (the last Sq positions); k,v [B,Hkv,Sk,D]; lse [B,Hq,Sq] fp32 or None; workspace: a
+    contiguous device tensor of at least decode_workspace_bytes(...) bytes.  Enqueues on `stream`.
+    """
+    import torch
+    for t in (q, k, v, o, workspace):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("q, k, v, o and workspace must be contiguous device tensors")
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    if tuple(k.shape) != (B, Hkv, Sk, D) or tuple(v.shape) != (B, Hkv, Sk, D) or tuple(o.shape) != (B, Hq, Sq, D):
+        raise ValueError("shape mismatch between q, k, v, o")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share one dtype")
+    lse_ptr = None
+    if lse is not None:
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, Hq, Sq)):
+            raise ValueError("lse must be a contiguous fp32 device tensor [B,Hq,Sq]")
+        lse_ptr = lse.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    in_dt, out_dt = _torch_dtype_code(q), _torch_dtype_code(o)
+    if in_dt == NAUT_BF16 and out_dt == NAUT_BF16:
+        rc = naut_attn_decode_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, Sq, Sk,
+                                  D, causal, scale, workspace.data_ptr(), ws_bytes, stream.cuda_stream)
+    else:
+        rc = naut_attn_decode_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, Sq, Sk,
+                                  D, causal, scale, workspace.data_ptr(), ws_bytes, stream.cuda_stream, in_dt, out_dt)
     if rc != NAUT_OK:
         raise NautError(rc, last_error_string())

@@ -7,7 +7,7 @@ import sys
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SRC = os.path.join(_HERE, "csrc", "naut_attn.hip")
+SRCS = [os.path.join(_HERE, "csrc", n) for n in ("naut_attn.hip", "naut_decode.hip")]
 LIB = os.path.join(_HERE, "libnaut_attn.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -25,7 +25,7 @@ FLAGS = [
 
 def build_lib(extra=(), verbose=False) -> str:
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + list(extra) + [SRC, "-o", tmp]
+    cmd = [HIPCC] + FLAGS + list(extra) + SRCS + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

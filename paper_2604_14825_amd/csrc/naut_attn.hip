@@ -34,21 +34,11 @@
 #include <type_traits>
 
 #include "naut_attn.h"
+#include "naut_common.h"
 
 namespace {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-typedef int i32x4_t __attribute__((ext_vector_type(4)));
-typedef int i32x2_t __attribute__((ext_vector_type(2)));
-typedef short i16x4_t __attribute__((ext_vector_type(4)));
-
-#define NAUT_LDS __attribute__((address_space(3)))
+using namespace naut;
 
 constexpr int BM = 128;  // queries per work-group
 constexpr int BN = 64;   // keys per step
@@ -68,100 +58,6 @@ struct Params {
     int nqt2;      // number of 256-query tiles
     float c;       // scale * log2(e), > 0
 };
-
-// ---- per-dtype pieces ------------------------------------------------------
-
-template <int DT>
-struct In;
-
-template <>
-struct In<NAUT_BF16> {
-    static __device__ __forceinline__ f32x16_t mfma(i32x4_t a, i32x4_t b, f32x16_t c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int pack2(float lo, float hi)
-    {
-        f32x2_t f = {lo, hi};
-        return __builtin_bit_cast(int, __builtin_convertvector(f, bf16x2_t));
-    }
-};
-
-template <>
-struct In<NAUT_F16> {
-    static __device__ __forceinline__ f32x16_t mfma(i32x4_t a, i32x4_t b, f32x16_t c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a),
-                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int pack2(float lo, float hi)
-    {
-        f32x2_t f = {lo, hi};
-        return __builtin_bit_cast(int, __builtin_convertvector(f, f16x2_t));
-    }
-};
-
-// ---- LDS layouts -------------------------------------------------------------
-// Both tiles hold BN rows of D 16-bit values.  Addresses are byte offsets inside
-// one tile; `c` counts 16-byte chunks inside a row.
-//
-// K is read as the MFMA A operand: 32 lanes read the same chunk of 32
-// consecutive rows, so the chunk position is XOR-ed with the 256-byte line
-// number to spread those reads over all banks.
-template <int D>
-__device__ __forceinline__ int k_off(int row, int c)
-{
-    constexpr int CPR = D / 8;  // chunks per row
-    const int L = row * CPR + c;
-    const int line = L >> 4, pos = L & 15;
-    return (line << 8) + ((pos ^ (line & 15)) << 4);
-}
-
-// V is read transposed: one wavefront-wide read touches 8 consecutive rows x 64
-// bytes, so the 64-byte quarter of the 256-byte line is XOR-ed with the row
-// number to put the rows of one read in different quarters.
-template <int D>
-__device__ __forceinline__ int v_off(int row, int c)
-{
-    if constexpr (D == 128)
-        return row * 256 + ((c ^ ((row & 3) << 2)) << 4);
-    else
-        return row * 128 + ((c ^ (((row >> 1) & 1) << 2)) << 4);
-}
-
-// 8 values V[key(slot)][d] for the MFMA A operand of the P.V product.
-// The lane owns output row d = 32*db + lane%32 and k-slots 8h..8h+7 (h = lane/32),
-// which stand for keys kbase + 4h + {0..3} and kbase + 8 + 4h + {0..3}.
-// ds_read_b64_tr_b16: within each 16-lane group, lane i supplies the address of 4 consecutive d of
-// key (i/4) and receives the 4 keys of d = i.
-template <int D>
-__device__ __forceinline__ i32x4_t load_vt_frag(const unsigned char* vt, int kbase, int db, int lane)
-{
-    const int h = lane >> 5;
-    const int i16 = lane & 15;
-    const int d = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-    const int key = kbase + 4 * h + (i16 >> 2);
-    const int a0 = v_off<D>(key, d >> 3) + (d & 7) * 2;
-    const int a1 = v_off<D>(key + 8, d >> 3) + (d & 7) * 2;
-    i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(vt + a0));
-    i16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(vt + a1));
-    i32x2_t lo = __builtin_bit_cast(i32x2_t, r0);
-    i32x2_t hi = __builtin_bit_cast(i32x2_t, r1);
-    i32x4_t out = {lo.x, lo.y, hi.x, hi.y};
-    return out;
-}
-
-// max over the two 32-lane halves.  v_permlane32_swap exchanges the upper 32 lanes of its first
-// operand with the lower 32 lanes of its second, so afterwards (a, b) = (x[lane%32], x[lane%32+32])
-// in every lane.  Written as inline asm: the compiler folds the two results of the corresponding
-// builtin into one.
-__device__ __forceinline__ float half_max(float x)
-{
-    float a = x, b = x;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-    return fmaxf(a, b);
-}
 
 // ---- kernel 1: 128 queries per work-group, 4 wavefronts x 32 queries, two work-groups per CU ----
 
@@ -1044,6 +940,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 
 // ---- host side ---------------------------------------------------------------------
 
+}  // namespace
+
+namespace naut {
+
 thread_local char g_err[256] = "";
 
 int fail(int code, const char* msg)
@@ -1051,6 +951,16 @@ int fail(int code, const char* msg)
     snprintf(g_err, sizeof g_err, "%s", msg);
     return code;
 }
+
+int fail_launch(hipError_t e)
+{
+    snprintf(g_err, sizeof g_err, "kernel launch failed: %s", hipGetErrorString(e));
+    return NAUT_ERR_HIP;
+}
+
+}  // namespace naut
+
+namespace {
 
 // Kernel variants (the tile shape / wavefront count / buffering choice the paper leaves to its
 // auto-tuner, Section 4.4 and Section 7.2).  NAUT_ATTN_VARIANT=w8q32|w4q64|bm128 overrides the
@@ -1110,10 +1020,8 @@ int launch(const Params& p, int causal, hipStream_t stream)
     }
 #undef NAUT_LAUNCH
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        snprintf(g_err, sizeof g_err, "kernel launch failed: %s", hipGetErrorString(e));
-        return NAUT_ERR_HIP;
-    }
+    if (e != hipSuccess)
+        return fail_launch(e);
     return NAUT_OK;
 }
 

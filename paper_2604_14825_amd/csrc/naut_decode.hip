@@ -1,0 +1,469 @@
+// naut_decode.hip -- decode-time attention for gfx950 (MI355X): a few new query positions per head
+// against a long key/value cache (the paper's second workload, "DC", Section 6).
+//
+// The work is bound by reading K and V once from HBM, not by the matrix pipes, so the key axis is
+// split across work-groups (and again across the four wavefronts of a work-group): every wavefront
+// streams its own 32-key blocks of K and V through a private double buffer in LDS with direct
+// global->LDS loads (no work-group barrier in the loop), runs the same transposed MFMA formulation
+// as the prefill kernels on them (S^T = K.Q^T, online softmax with a lazily moved reference maximum,
+// O^T += V^T.P^T), and the partial (O, m, l) triples are merged with the split-merge identity of
+// softmax, first across the wavefronts through LDS, then across the splits by a second small kernel
+// that reads them from a caller-provided workspace.
+//
+// Query heads that share a K/V head (grouped-query attention) and the Sq positions of each form the
+// rows of one MFMA tile: for a fixed (batch, K/V head) the Hq/Hkv * Sq query rows are contiguous in
+// memory, so they are simply rows 0..R-1 of a [R][D] matrix, taken 32 at a time.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+
+#include "naut_attn.h"
+#include "naut_common.h"
+
+namespace {
+
+using namespace naut;
+
+constexpr int DEC_WAVES = 4;
+constexpr int DEC_THREADS = DEC_WAVES * 64;
+constexpr int DEC_ROWS = 32;               // query rows per work-group (one MFMA tile)
+constexpr int DEC_BLK = 32;                // keys per block
+constexpr float DEC_TAU = 6.0f;            // the reference maximum moves when a row exceeds it by 2^6
+constexpr float DEC_M_INIT = -1.0e30f;     // finite stand-in for "no maximum yet"
+constexpr int DEC_TARGET_WGS = 1024;       // about four work-groups per CU
+
+struct DecodeParams {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    float* lse;
+    float* ws;     // workspace: partial O [nparts][32][D], then m [nparts][32], then l [nparts][32]
+    int B, Hq, Hkv, Sq, Sk;
+    int R;         // query rows per (batch, K/V head) = Hq/Hkv * Sq
+    int nchunks;   // ceil(R / 32)
+    int nsplit;    // splits of the key axis
+    int bps;       // 32-key blocks per split (a multiple of 4)
+    int causal;
+    float c;       // scale * log2(e), > 0
+};
+
+__device__ __forceinline__ float half_sum_f(float x)
+{
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
+}
+
+template <int D, int DT_IN>
+__global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const DecodeParams p)
+{
+    using T = In<DT_IN>;
+    constexpr int ROWB = D * 2;
+    constexpr int BLKB = DEC_BLK * ROWB;   // one 32-key block of K or V
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int NLD = BLKB / 1024;       // direct loads (1 KB each) per block and operand
+    constexpr int OSTRIDE = D + 4;         // floats per row of the partial O in LDS (padded against bank conflicts)
+    static_assert(DEC_ROWS * OSTRIDE * 4 + 2 * DEC_ROWS * 4 <= 4 * BLKB, "the wavefront's partial fits its LDS region");
+
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[DEC_WAVES * 4 * BLKB];  // per wavefront: K0 V0 K1 V1
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+
+    const int split = blockIdx.x, chunk = blockIdx.y, bhk = blockIdx.z;
+    const int b = bhk / p.Hkv, hk = bhk % p.Hkv;
+    const int g = p.Hq / p.Hkv;
+    const int Sk = p.Sk;
+    const float c = p.c;
+
+    // The R rows of this (batch, K/V head) are contiguous: [R][D] starting at query head hk*g.
+    const unsigned char* qg = (const unsigned char*)p.q + (size_t)(b * p.Hq + hk * g) * p.Sq * ROWB;
+    const unsigned char* kg = (const unsigned char*)p.k + (size_t)bhk * Sk * ROWB;
+    const unsigned char* vg = (const unsigned char*)p.v + (size_t)bhk * Sk * ROWB;
+
+    const int row = chunk * DEC_ROWS + l32;                 // the query row this lane owns
+    const int row_ld = row < p.R ? row : p.R - 1;
+    // last key this row may see: the Sq queries are the last positions of a sequence of Sk
+    const int lim = p.causal ? Sk - p.Sq + (row_ld % p.Sq) : Sk - 1;
+
+    i32x4_t qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        qf[ks] = *(const i32x4_t*)(qg + (size_t)row_ld * ROWB + ks * 32 + h * 16);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        asm volatile("" : "+v"(qf[ks]));
+
+    // Direct global->LDS loads: instruction n fills physical chunks 64n..64n+63 of the block, lane i
+    // the chunk 64n+i, so the lane fetches the logical chunk that the swizzle maps there.
+    int k_go[NLD], v_go[NLD];
+#pragma unroll
+    for (int n = 0; n < NLD; ++n) {
+        const int P = n * 64 + lane;
+        {
+            const int line = P >> 4, pos = P & 15;
+            k_go[n] = ((line << 4) + (pos ^ (line & 15))) * 16;
+        }
+        if constexpr (D == 128) {
+            const int r = P >> 4, cc = P & 15;
+            v_go[n] = r * ROWB + (cc ^ ((r & 3) << 2)) * 16;
+        } else {
+            const int r = P >> 3, cc = P & 7;
+            v_go[n] = r * ROWB + (cc ^ (((r >> 1) & 1) << 2)) * 16;
+        }
+    }
+    const unsigned lds0 = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem + (unsigned)(wave * 4 * BLKB);
+    unsigned char* my_lds = smem + wave * 4 * BLKB;
+
+    const int nblk = (Sk + DEC_BLK - 1) / DEC_BLK;
+    const int blk_begin = split * p.bps;
+    const int blk_end = blk_begin + p.bps < nblk ? blk_begin + p.bps : nblk;
+
+    auto issue = [&](int blk, int buf) {
+        const unsigned char* kp = kg + (size_t)blk * BLKB;
+        const unsigned char* vp = vg + (size_t)blk * BLKB;
+        const int rows_left = Sk - blk * DEC_BLK;  // >= 1
+        const unsigned dst = lds0 + (unsigned)(buf * 2 * BLKB);
+#pragma unroll
+        for (int n = 0; n < NLD; ++n) {
+            int ko = k_go[n], vo = v_go[n];
+            if (rows_left < DEC_BLK) {  // ragged last block: re-read the last row instead of running past the end
+                ko = ko / ROWB < rows_left ? ko : (rows_left - 1) * ROWB + ko % ROWB;
+                vo = vo / ROWB < rows_left ? vo : (rows_left - 1) * ROWB + vo % ROWB;
+            }
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst + n * 1024), "v"(ko), "s"(kp)
+                         : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst + BLKB + n * 1024), "v"(vo), "s"(vp)
+                         : "memory", "m0");
+        }
+    };
+
+    f32x16_t oacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            oacc[db][r] = 0.f;
+    float m_run = DEC_M_INIT;  // reference maximum, log2 units (already times c)
+    float l_run = 0.f;         // this lane's share of the running sum (its 16 of every 32 keys)
+
+    // This wavefront's blocks: blk_begin + wave, + 4, ...  Block n+1 is in flight while block n is used.
+    int blk = blk_begin + wave;
+    if (blk < blk_end)
+        issue(blk, 0);
+    for (int it = 0; blk < blk_end; blk += DEC_WAVES, ++it) {
+        const int buf = it & 1;
+        const bool more = blk + DEC_WAVES < blk_end;
+        if (more) {
+            issue(blk + DEC_WAVES, buf ^ 1);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NLD) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        const unsigned char* kt = my_lds + buf * 2 * BLKB;
+        const unsigned char* vt = kt + BLKB;
+
+        f32x16_t s_;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            s_[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const i32x4_t kf = *(const i32x4_t*)(kt + k_off<D>(l32, ks * 2 + h));
+            s_ = T::mfma(kf, qf[ks], s_);
+        }
+        const int key0 = blk * DEC_BLK;
+        if (key0 + DEC_BLK - 1 > Sk - p.Sq || key0 + DEC_BLK > Sk) {  // some row's limit may fall inside the block
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + 8 * (r >> 2) + 4 * h + (r & 3);
+                s_[r] = key > lim ? -INFINITY : s_[r];
+            }
+        }
+        float mx = s_[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r)
+            mx = fmaxf(mx, s_[r]);
+        mx = half_max(mx);
+        const float m_cand = mx * c;  // -inf if the whole block is masked for this row
+        if (__builtin_amdgcn_ballot_w64(m_cand > m_run + DEC_TAU) != 0) {
+            const float m_new = fmaxf(m_run, m_cand);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // repair factor
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    oacc[db][r] *= alpha;
+        }
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            s_[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[r], c, -m_run));
+            psum += s_[r];
+        }
+        l_run += psum;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int r0 = t * 8;
+            const i32x4_t pb = {T::pack2(s_[r0 + 0], s_[r0 + 1]), T::pack2(s_[r0 + 2], s_[r0 + 3]),
+                                T::pack2(s_[r0 + 4], s_[r0 + 5]), T::pack2(s_[r0 + 6], s_[r0 + 7])};
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const i32x4_t vf = load_vt_frag<D>(vt, t * 16, db, lane);
+                oacc[db] = T::mfma(vf, pb, oacc[db]);
+            }
+        }
+    }
+
+    // ---- merge the four wavefronts through LDS (each reuses its own, now idle, region) ----
+    float* my_o = (float*)my_lds;                          // [32][OSTRIDE]
+    float* my_ml = my_o + DEC_ROWS * OSTRIDE;              // m[32], l[32]
+    const float l_tot = half_sum_f(l_run);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const int d = 32 * db + 8 * gq + 4 * h;
+            const f32x4_t w = {oacc[db][4 * gq + 0], oacc[db][4 * gq + 1], oacc[db][4 * gq + 2], oacc[db][4 * gq + 3]};
+            *(f32x4_t*)(my_o + l32 * OSTRIDE + d) = w;
+        }
+    if (h == 0) {
+        my_ml[l32] = m_run;
+        my_ml[DEC_ROWS + l32] = l_tot;
+    }
+    __syncthreads();
+
+    // thread -> (row, D/8 consecutive d); partial written to the workspace
+    constexpr int DPT = D / 8;  // floats per thread: 16 (D = 128) or 8 (D = 64)
+    const int r_out = tid >> 3, d0 = (tid & 7) * DPT;
+    float mw[DEC_WAVES], lw[DEC_WAVES];
+    float M = DEC_M_INIT;
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) {
+        const float* ml = (const float*)(smem + w * 4 * BLKB) + DEC_ROWS * OSTRIDE;
+        mw[w] = ml[r_out];
+        lw[w] = ml[DEC_ROWS + r_out];
+        M = fmaxf(M, mw[w]);
+    }
+    float L = 0.f;
+    f32x4_t acc[DPT / 4];
+#pragma unroll
+    for (int i = 0; i < DPT / 4; ++i)
+        acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) {
+        const float f = __builtin_amdgcn_exp2f(mw[w] - M);
+        L += f * lw[w];
+        const float* ow = (const float*)(smem + w * 4 * BLKB) + r_out * OSTRIDE + d0;
+#pragma unroll
+        for (int i = 0; i < DPT / 4; ++i) {
+            const f32x4_t x = *(const f32x4_t*)(ow + 4 * i);
+            acc[i] += x * f;
+        }
+    }
+    const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
+    const size_t part = ((size_t)bhk * p.nchunks + chunk) * p.nsplit + split;
+    float* ws_o = p.ws + (part * DEC_ROWS + r_out) * D + d0;
+#pragma unroll
+    for (int i = 0; i < DPT / 4; ++i)
+        *(f32x4_t*)(ws_o + 4 * i) = acc[i];
+    if ((tid & 7) == 0) {
+        float* ws_m = p.ws + nparts * DEC_ROWS * D;
+        float* ws_l = ws_m + nparts * DEC_ROWS;
+        ws_m[part * DEC_ROWS + r_out] = M;
+        ws_l[part * DEC_ROWS + r_out] = L;
+    }
+}
+
+// One wavefront per query row: merges the nsplit partials of the row, divides by l once, stores O and lse.
+template <int D, int DT_OUT>
+__global__ __launch_bounds__(64) void naut_decode_merge_kernel(const DecodeParams p)
+{
+    const int lane = threadIdx.x;
+    const int r = blockIdx.x;    // row inside the (batch, K/V head): 0 .. nchunks*32-1
+    const int bhk = blockIdx.y;
+    if (r >= p.R)
+        return;
+    const int chunk = r / DEC_ROWS, rr = r % DEC_ROWS;
+    const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
+    const size_t part0 = ((size_t)bhk * p.nchunks + chunk) * p.nsplit;
+    const float* ws_m = p.ws + nparts * DEC_ROWS * D;
+    const float* ws_l = ws_m + nparts * DEC_ROWS;
+    float M = DEC_M_INIT;
+    for (int s = 0; s < p.nsplit; ++s)
+        M = fmaxf(M, ws_m[(part0 + s) * DEC_ROWS + rr]);
+    constexpr int EPT = D / 64;  // elements per lane
+    float acc[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+        acc[e] = 0.f;
+    float L = 0.f;
+    for (int s = 0; s < p.nsplit; ++s) {
+        const float f = __builtin_amdgcn_exp2f(ws_m[(part0 + s) * DEC_ROWS + rr] - M);
+        L += f * ws_l[(part0 + s) * DEC_ROWS + rr];
+        const float* po = p.ws + ((part0 + s) * DEC_ROWS + rr) * D + lane * EPT;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            acc[e] += f * po[e];
+    }
+    const float inv_l = 1.0f / L;
+    // global row index: the R rows of (batch, K/V head) bhk are contiguous in o and lse
+    const size_t grow = (size_t)bhk * p.R + r;
+    if (p.lse != nullptr && lane == 0)
+        p.lse[grow] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
+    if constexpr (DT_OUT == NAUT_F32) {
+        float* og = (float*)p.o + grow * D + lane * EPT;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            og[e] = acc[e] * inv_l;
+    } else if constexpr (EPT == 2) {
+        int* og = (int*)((unsigned char*)p.o + (grow * D + lane * EPT) * 2);
+        *og = In<DT_OUT>::pack2(acc[0] * inv_l, acc[1] * inv_l);
+    } else {
+        unsigned short* og = (unsigned short*)p.o + grow * D + lane;
+        *og = (unsigned short)(In<DT_OUT>::pack2(acc[0] * inv_l, 0.f) & 0xffff);
+    }
+}
+
+struct Plan {
+    int nchunks, nsplit, bps;
+    size_t ws_bytes;
+};
+
+bool make_plan(int B, int Hq, int Hkv, int Sq, int Sk, int D, Plan* pl)
+{
+    const long long R = (long long)(Hq / Hkv) * Sq;
+    const long long nchunks = (R + DEC_ROWS - 1) / DEC_ROWS;
+    const long long nblk = ((long long)Sk + DEC_BLK - 1) / DEC_BLK;
+    const long long base = (long long)B * Hkv * nchunks;
+    long long nsplit = (DEC_TARGET_WGS + base - 1) / base;
+    const long long max_split = (nblk + 2 * DEC_WAVES - 1) / (2 * DEC_WAVES);  // at least two blocks per wavefront
+    nsplit = nsplit > max_split ? max_split : nsplit;
+    nsplit = nsplit < 1 ? 1 : nsplit;
+    long long bps = (nblk + nsplit - 1) / nsplit;
+    bps = (bps + DEC_WAVES - 1) / DEC_WAVES * DEC_WAVES;
+    nsplit = (nblk + bps - 1) / bps;
+    if (nchunks > 65535 || (long long)B * Hkv > 65535 || nsplit > 0x7fffffffLL || nchunks * DEC_ROWS > 0x7fffffffLL)
+        return false;
+    pl->nchunks = (int)nchunks;
+    pl->nsplit = (int)nsplit;
+    pl->bps = (int)bps;
+    pl->ws_bytes = (size_t)(base * nsplit) * DEC_ROWS * (D + 2) * sizeof(float);
+    return true;
+}
+
+template <int D, int DT_IN, int DT_OUT>
+int launch_decode(const DecodeParams& p, hipStream_t stream)
+{
+    const dim3 g1((unsigned)p.nsplit, (unsigned)p.nchunks, (unsigned)(p.B * p.Hkv));
+    hipLaunchKernelGGL((naut_decode_split_kernel<D, DT_IN>), g1, dim3(DEC_THREADS), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_launch(e);
+    const dim3 g2((unsigned)(p.nchunks * DEC_ROWS), (unsigned)(p.B * p.Hkv));
+    hipLaunchKernelGGL((naut_decode_merge_kernel<D, DT_OUT>), g2, dim3(64), 0, stream, p);
+    e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_launch(e);
+    return NAUT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D)
+{
+    Plan pl;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || Hq % Hkv != 0 || (D != 64 && D != 128) ||
+        !make_plan(B, Hq, Hkv, Sq, Sk, D, &pl))
+        return 0;
+    return pl.ws_bytes;
+}
+
+int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                        int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
+                        void* stream, int in_dtype, int out_dtype)
+{
+    if (!q || !k || !v || !o)
+        return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || D <= 0)
+        return fail(NAUT_ERR_SHAPE, "B, Hq, Hkv, Sq, Sk and D must be positive");
+    if (Hq % Hkv != 0)
+        return fail(NAUT_ERR_SHAPE, "Hq must be a multiple of Hkv");
+    if (causal && Sk < Sq)
+        return fail(NAUT_ERR_SHAPE, "with the causal mask the Sq queries are the last positions of Sk: Sk >= Sq");
+    if (!std::isfinite(scale))
+        return fail(NAUT_ERR_SHAPE, "scale must be finite");
+    if (scale < 0.f)
+        return fail(NAUT_ERR_UNSUPPORTED, "negative scale is not supported");
+    if (D != 64 && D != 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    if ((in_dtype != NAUT_BF16 && in_dtype != NAUT_F16) || (out_dtype != in_dtype && out_dtype != NAUT_F32))
+        return fail(NAUT_ERR_UNSUPPORTED, "supported dtypes: q/k/v bf16 or f16; o of the same type or f32");
+    Plan pl;
+    if (!make_plan(B, Hq, Hkv, Sq, Sk, D, &pl))
+        return fail(NAUT_ERR_UNSUPPORTED, "shape exceeds the grid limits");
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)workspace) & 15)
+        return fail(NAUT_ERR_ALIGN, "q, k, v, o and workspace must be 16-byte aligned");
+    if ((uintptr_t)lse & 3)
+        return fail(NAUT_ERR_ALIGN, "lse must be 4-byte aligned");
+    if (!workspace || workspace_bytes < pl.ws_bytes)
+        return fail(NAUT_ERR_SHAPE, "workspace is NULL or smaller than naut_attn_decode_workspace_bytes()");
+
+    DecodeParams p;
+    p.q = q;
+    p.k = k;
+    p.v = v;
+    p.o = o;
+    p.lse = lse;
+    p.ws = (float*)workspace;
+    p.B = B;
+    p.Hq = Hq;
+    p.Hkv = Hkv;
+    p.Sq = Sq;
+    p.Sk = Sk;
+    p.R = Hq / Hkv * Sq;
+    p.nchunks = pl.nchunks;
+    p.nsplit = pl.nsplit;
+    p.bps = pl.bps;
+    p.causal = causal ? 1 : 0;
+    const float cc = scale * 1.4426950408889634f;
+    p.c = cc > 0.f ? cc : 1.0e-30f;  // scale == 0: every score becomes (almost exactly) 0, the softmax uniform
+    hipStream_t st = (hipStream_t)stream;
+#define NAUT_DEC(DD, IN, OUT)                                  \
+    if (D == DD && in_dtype == IN && out_dtype == OUT)         \
+        return launch_decode<DD, IN, OUT>(p, st);
+    NAUT_DEC(128, NAUT_BF16, NAUT_BF16)
+    NAUT_DEC(128, NAUT_BF16, NAUT_F32)
+    NAUT_DEC(128, NAUT_F16, NAUT_F16)
+    NAUT_DEC(128, NAUT_F16, NAUT_F32)
+    NAUT_DEC(64, NAUT_BF16, NAUT_BF16)
+    NAUT_DEC(64, NAUT_BF16, NAUT_F32)
+    NAUT_DEC(64, NAUT_F16, NAUT_F16)
+    NAUT_DEC(64, NAUT_F16, NAUT_F32)
+#undef NAUT_DEC
+    return fail(NAUT_ERR_UNSUPPORTED, "no kernel for this (D, dtype) combination");
+}
+
+int naut_attn_decode(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int Sq,
+                     int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return naut_attn_decode_dt(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale, workspace, workspace_bytes, stream,
+                               NAUT_BF16, NAUT_BF16);
+}
+
+}  // extern "C"

@@ -57,3 +57,20 @@ def sample_rows(w, n_random, seed, bm=128):
     for r in g.integers(0, nbh * S, n_random):
         rows.add(int(r))
     return np.array(sorted(rows), dtype=np.int64)
+
+
+def run_hip_decode(q, k, v, in_dtype, out_dtype, causal, scale, want_lse=True, poison_workspace=True):
+    """Decode-time attention through the C ABI.  q [B,Hq,Sq,D], k,v [B,Hkv,Sk,D] uint16 numpy arrays."""
+    qd, kd, vd = (to_device(a, in_dtype) for a in (q, k, v))
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    o = torch.full((B, Hq, Sq, D), float("nan"), dtype=TORCH_DT[out_dtype], device="cuda")
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    nbytes = nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    if poison_workspace:
+        ws.fill_(0xFF)  # NaN patterns: every partial the merge reads must have been written by the first kernel
+    nb.naut_attn_decode(qd, kd, vd, o, lse, causal, scale, ws)
+    torch.cuda.synchronize()
+    return o.double().cpu().numpy(), (lse.double().cpu().numpy() if want_lse else None)

@@ -92,3 +92,29 @@ def test_missing_library_is_loud(monkeypatch, tmp_path):
     monkeypatch.setattr(nb, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         nb.lib()
+
+
+def test_decode_argument_checks():
+    """Validation of the decode entry point runs on the host before any HIP call."""
+    ws = nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 128)
+    assert ws > 0 and ws % 16 == 0
+    assert nb.decode_workspace_bytes(1, 8, 3, 1, 4096, 128) == 0   # Hq % Hkv
+    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 96) == 0    # D
+    ok = dict(B=1, Hq=8, Hkv=2, Sq=1, Sk=4096, D=128, causal=1, scale=0.1)
+
+    def dec(q=A, k=A, v=A, o=A, lse=A, wsp=A, wsb=ws, **kw):
+        a = dict(ok)
+        a.update(kw)
+        return nb.naut_attn_decode_raw(q, k, v, o, lse, a["B"], a["Hq"], a["Hkv"], a["Sq"], a["Sk"], a["D"], a["causal"],
+                                       a["scale"], wsp, wsb, None)
+    assert dec(q=None) == nb.NAUT_ERR_NULL
+    assert dec(Sk=0) == nb.NAUT_ERR_SHAPE
+    assert dec(Hkv=3) == nb.NAUT_ERR_SHAPE
+    assert dec(Sq=5000) == nb.NAUT_ERR_SHAPE            # causal needs Sk >= Sq
+    assert dec(scale=float("inf")) == nb.NAUT_ERR_SHAPE
+    assert dec(scale=-1.0) == nb.NAUT_ERR_UNSUPPORTED
+    assert dec(D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert dec(k=A + 8) == nb.NAUT_ERR_ALIGN
+    assert dec(wsp=None) == nb.NAUT_ERR_SHAPE
+    assert dec(wsb=ws - 1) == nb.NAUT_ERR_SHAPE
+    assert "workspace" in nb.last_error_string()

@@ -1,0 +1,103 @@
+"""GPU parity of decode-time attention (through the C ABI) against the fp64 oracle on identical seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_14825_amd import binding as nb
+from paper_2604_14825_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # B, Hq, Hkv, Sq, Sk, D, causal, in, out   (R = Hq/Hkv*Sq rows share a K/V head; 32 rows per work-group)
+    (1, 1, 1, 1, 1, 64, False, synth.BF16, synth.BF16),        # one key
+    (1, 2, 2, 1, 31, 128, True, synth.BF16, synth.BF16),       # less than one block
+    (1, 4, 4, 1, 100, 128, True, synth.BF16, synth.BF16),      # ragged last block
+    (2, 8, 2, 1, 777, 128, True, synth.BF16, synth.F32),       # grouped-query, R = 4
+    (1, 8, 1, 3, 500, 64, True, synth.F16, synth.F16),         # R = 24, three positions, D = 64
+    (1, 16, 2, 5, 300, 128, True, synth.BF16, synth.BF16),     # R = 40: two row chunks
+    (1, 2, 2, 1, 4096, 128, False, synth.BF16, synth.BF16),    # many splits
+    (1, 2, 1, 64, 64, 64, True, synth.BF16, synth.F32),        # Sq == Sk: plain causal self-attention, R = 128
+    (2, 4, 4, 7, 1000, 64, False, synth.F16, synth.F32),       # no mask, several positions
+    (3, 6, 3, 2, 2049, 128, True, synth.BF16, synth.BF16),     # odd sizes everywhere
+]
+
+
+def make(B, Hq, Hkv, Sq, Sk, D, idt, seed, n_outlier=0):
+    q = synth.fill(B, Hq, Sq, D, seed, synth.TAG_Q, idt)
+    k = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_K, idt, n_outlier, 8.0)
+    v = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_V, idt)
+    return q, k, v
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal,idt,odt", CASES)
+def test_decode_elementwise(B, Hq, Hkv, Sq, Sk, D, causal, idt, odt):
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, idt, 7000 + Sk + D + Sq, Sk // 50)
+    scale = 1.0 / math.sqrt(D)
+    print("decode case", B, Hq, Hkv, Sq, Sk, D, causal, idt, odt, flush=True)
+    o, lse = gu.run_hip_decode(q, k, v, idt, odt, causal, scale)
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, causal, scale)
+    gu.check(o, lse, o_ref, lse_ref, "decode")
+
+
+def test_decode_long_cache_gqa():
+    """A cache of the benchmark's length: B=2, 32 query heads on 8 K/V heads, one new position, Sk = 16384."""
+    B, Hq, Hkv, Sq, Sk, D = 2, 32, 8, 1, 16384, 128
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, synth.BF16, 7777, Sk // 100)
+    scale = 1.0 / math.sqrt(D)
+    o, lse = gu.run_hip_decode(q, k, v, synth.BF16, synth.BF16, True, scale)
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, synth.BF16, True, scale)
+    gu.check(o, lse, o_ref, lse_ref, "decode long")
+
+
+def test_decode_matches_prefill_tail():
+    """The last Sq rows of the prefill kernel's causal self-attention and the decode path agree with the
+    oracle (and hence with each other to twice the tolerance)."""
+    B, Hq, Hkv, S, D, Sq = 1, 4, 2, 640, 128, 4
+    q, k, v = make(B, Hq, Hkv, S, S, D, synth.BF16, 7100)
+    scale = 1.0 / math.sqrt(D)
+    o_full, lse_full = gu.run_hip(q, k, v, synth.BF16, synth.F32, True, scale)
+    o_dec, lse_dec = gu.run_hip_decode(np.ascontiguousarray(q[:, :, S - Sq:]), k, v, synth.BF16, synth.F32, True, scale)
+    assert np.abs(o_dec - o_full[:, :, S - Sq:]).max() <= 2 * gu.TOL_MAX
+    assert np.abs(lse_dec - lse_full[:, :, S - Sq:]).max() <= 2e-3 * np.maximum(1.0, np.abs(lse_dec)).max()
+    o_ref, lse_ref = oracle.attn_cross16(np.ascontiguousarray(q[:, :, S - Sq:]), k, v, synth.BF16, True, scale)
+    gu.check(o_dec, lse_dec, o_ref, lse_ref, "decode tail")
+
+
+def test_decode_moving_maximum_and_hot_softmax():
+    """Keys that grow along the cache (the reference maximum keeps moving inside every split, and differs
+    wildly between splits) at four times the usual softmax temperature."""
+    B, Hq, Hkv, Sq, Sk, D = 1, 8, 2, 2, 3000, 128
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, synth.BF16, 7200)
+    kf = (k.astype(np.uint32) << 16).view(np.float32) * (0.25 + 12.0 * np.arange(Sk, dtype=np.float32) / (Sk - 1))[None, None, :, None]
+    k = synth.round16(kf, synth.BF16)
+    scale = 4.0 / math.sqrt(D)
+    o, lse = gu.run_hip_decode(q, k, v, synth.BF16, synth.F32, True, scale)
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, synth.BF16, True, scale)
+    gu.check(o, lse, o_ref, lse_ref, "decode ascending")
+
+
+def test_decode_bit_identical_and_lse_optional():
+    B, Hq, Hkv, Sq, Sk, D = 2, 8, 4, 1, 5000, 128
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, synth.BF16, 7300)
+    scale = 1.0 / math.sqrt(D)
+    o1, l1 = gu.run_hip_decode(q, k, v, synth.BF16, synth.BF16, True, scale)
+    o2, _ = gu.run_hip_decode(q, k, v, synth.BF16, synth.BF16, True, scale, want_lse=False, poison_workspace=False)
+    assert np.array_equal(o1, o2)
+
+
+def test_decode_rejects_short_workspace():
+    B, Hq, Hkv, Sq, Sk, D = 1, 2, 2, 1, 1024, 128
+    q = torch.zeros((B, Hq, Sq, D), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((B, Hkv, Sk, D), dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros_like(q)
+    need = nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D)
+    ws = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(nb.NautError) as e:
+        nb.naut_attn_decode(q, k, k, o, None, True, 0.1, ws)
+    assert e.value.code == nb.NAUT_ERR_SHAPE
