@@ -31,7 +31,15 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16/fp16 MFMA: 256 CU x 4096 FLOP/clk
 MEASURED_TRAFFIC_BYTES = {
     # profiles/naut_fwd_bm256_w8q32_long_S16384_D128_causal.md: 716246 KiB x 2.000 read + 133135 KiB x 1.000 written
     "long": 1.603e9,
+    # profiles/naut_decode_B8_Hq32_Hkv8_Sk16384_D128.md: (262347 + 407) KiB x 2.000 read + (528 + 72) KiB written
+    "decode": 5.387e8,
 }
+
+PEAK_HBM_GBS = 8000.0  # MI355X HBM3E
+
+# Decode-time workload (the paper's second workload, Section 6): one new position per sequence against a
+# 16k-token key/value cache, 32 query heads on 8 K/V heads (a Qwen/GLM-like layout), B = 8.
+DECODE = {"B": 8, "Hq": 32, "Hkv": 8, "Sq": 1, "Sk": 16384, "D": 128, "outlier_frac": 0.01, "outlier_scale": 8.0}
 
 PAPER_CONTEXT = ("paper reports relative gains only: up to 23% over state-of-the-art compilers on GH200 and "
                  "up to 42% on RTX 5090 (FP16/FP8, other hardware) -- context, not a target")
@@ -104,12 +112,84 @@ def cpu_baseline(w, q, k, v, target_seconds: float):
     }
 
 
+def bench_decode(args, nb, synth, torch, np) -> int:
+    """One step = one naut_attn_decode call (split kernel + merge kernel) over the resident cache."""
+    c = DECODE
+    B, Hq, Hkv, Sq, Sk, D = c["B"], c["Hq"], c["Hkv"], c["Sq"], c["Sk"], c["D"]
+    seed = synth.BASE_SEED + 100
+    q = synth.fill(B, Hq, Sq, D, seed, synth.TAG_Q, synth.BF16)
+    k = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_K, synth.BF16, int(c["outlier_frac"] * Sk), c["outlier_scale"])
+    v = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_V, synth.BF16)
+    dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    qd, kd, vd = dev(q), dev(k), dev(v)
+    o = torch.empty((B, Hq, Sq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, Hq, Sq), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    scale = D ** -0.5
+
+    def step():
+        nb.naut_attn_decode(qd, kd, vd, o, lse, True, scale, ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    t0 = time.perf_counter()
+    ev.record(e0, stream.cuda_stream)
+    for _ in range(args.steps):
+        step()
+    ev.record(e1, stream.cuda_stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_wall = (t1 - t0) * 1e3 / args.steps
+    ms_kernel = ev.elapsed_ms(e0, e1) / args.steps
+    # algorithmic bytes: Q, K, V read once; O and LSE written once (the partials in the workspace are extra)
+    nbytes = (B * Hq * Sq * D + 2 * B * Hkv * Sk * D) * 2 + B * Hq * Sq * D * 2 + B * Hq * Sq * 4
+    out = {
+        "metric": "decode attention GB/s (B=8, 32/8 heads, Sk=16k, D=128)",
+        "value": nbytes / (ms_wall * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_wall,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "decode", "B": B, "Hq": Hq, "Hkv": Hkv, "Sq": Sq, "Sk": Sk, "D": D, "causal": True,
+                   "outlier_k_rows": int(c["outlier_frac"] * Sk), "kernel": "decode_split32x32 + merge",
+                   "workspace_bytes": int(ws.numel())},
+        "roofline": {"bound": "hbm", "achieved": nbytes / (ms_kernel * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": nbytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get("decode"), "kernel_ms": ms_kernel,
+                     "algorithmic_hbm_bytes": nbytes},
+        "context": PAPER_CONTEXT,
+    }
+    if args.cpu_seconds > 0 and args.cpu_rows != 0:
+        import oracle
+        # the whole workload is well under a second of CPU work, so the sample is all of it
+        nb_s = B
+        t0 = time.perf_counter()
+        oracle.attn_cross16(q[:nb_s], k[:nb_s], v[:nb_s], synth.BF16, True, scale)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": nbytes * nb_s / B / dt / 1e9, "unit": "GB/s", "cores": int(oracle.threads()),
+                               "kind": "oracle", "sample": "%d of %d batch entries, %.2f s wall incl. fp64 decode of K,V"
+                               % (nb_s, B, dt), "seconds": dt}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long")
+    ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long, or decode (a second, "
+                    "HBM-bound path: naut_attn_decode)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="seconds of CPU work the oracle baseline sample is sized for (0 = skip)")
     ap.add_argument("--cpu-rows", type=int, default=None, help="deprecated spelling: 0 skips the oracle baseline")
@@ -142,6 +222,9 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 5}))
         return 0
+
+    if args.workload == "decode":
+        return bench_decode(args, nb, synth, torch, np)
 
     w = synth.WORKLOADS[args.workload]
     q, k, v = synth.make_inputs(w)

@@ -26,13 +26,21 @@ namespace {
 
 using namespace naut;
 
-constexpr int DEC_WAVES = 4;
+#ifndef NAUT_DEC_WAVES
+#define NAUT_DEC_WAVES 4
+#endif
+constexpr int DEC_WAVES = NAUT_DEC_WAVES;  // wavefronts of the split kernel, each with a private 4-block LDS region
 constexpr int DEC_THREADS = DEC_WAVES * 64;
+constexpr int MRG_WAVES = 4;               // wavefronts of the merge kernel
+constexpr int MRG_THREADS = MRG_WAVES * 64;
 constexpr int DEC_ROWS = 32;               // query rows per work-group (one MFMA tile)
 constexpr int DEC_BLK = 32;                // keys per block
 constexpr float DEC_TAU = 6.0f;            // the reference maximum moves when a row exceeds it by 2^6
 constexpr float DEC_M_INIT = -1.0e30f;     // finite stand-in for "no maximum yet"
-constexpr int DEC_TARGET_WGS = 1024;       // about four work-groups per CU
+#ifndef NAUT_DEC_TARGET
+#define NAUT_DEC_TARGET 256
+#endif
+constexpr int DEC_TARGET_WGS = NAUT_DEC_TARGET;  // one work-group per CU: only one is resident at a time (LDS), and a single round measured fastest (256..1024 tried)
 
 struct DecodeParams {
     const void* q;
@@ -247,6 +255,8 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     __syncthreads();
 
     // thread -> (row, D/8 consecutive d); partial written to the workspace
+    if (tid >= DEC_ROWS * 8)
+        return;
     constexpr int DPT = D / 8;  // floats per thread: 16 (D = 128) or 8 (D = 64)
     const int r_out = tid >> 3, d0 = (tid & 7) * DPT;
     float mw[DEC_WAVES], lw[DEC_WAVES];
@@ -276,6 +286,8 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     }
     const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
     const size_t part = ((size_t)bhk * p.nchunks + chunk) * p.nsplit + split;
+    if (chunk * DEC_ROWS + r_out >= p.R)
+        return;  // rows past the last one are padding: nobody reads their partials
     float* ws_o = p.ws + (part * DEC_ROWS + r_out) * D + d0;
 #pragma unroll
     for (int i = 0; i < DPT / 4; ++i)
@@ -288,37 +300,64 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     }
 }
 
-// One wavefront per query row: merges the nsplit partials of the row, divides by l once, stores O and lse.
+// One work-group (four wavefronts) per query row: merges the nsplit partials of the row, divides by l
+// once, stores O and lse.  Wavefront w takes splits w, w+4, ...; lanes run over D.
 template <int D, int DT_OUT>
-__global__ __launch_bounds__(64) void naut_decode_merge_kernel(const DecodeParams p)
+__global__ __launch_bounds__(MRG_THREADS) void naut_decode_merge_kernel(const DecodeParams p)
 {
-    const int lane = threadIdx.x;
-    const int r = blockIdx.x;    // row inside the (batch, K/V head): 0 .. nchunks*32-1
+    __shared__ float red_m[MRG_WAVES];
+    __shared__ float red_l[MRG_WAVES];
+    __shared__ float red_o[MRG_WAVES][D];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = blockIdx.x;    // row inside the (batch, K/V head): 0 .. R-1
     const int bhk = blockIdx.y;
-    if (r >= p.R)
-        return;
     const int chunk = r / DEC_ROWS, rr = r % DEC_ROWS;
     const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
     const size_t part0 = ((size_t)bhk * p.nchunks + chunk) * p.nsplit;
-    const float* ws_m = p.ws + nparts * DEC_ROWS * D;
+    const float* ws_m = p.ws + nparts * DEC_ROWS * D + part0 * DEC_ROWS + rr;   // stride DEC_ROWS per split
     const float* ws_l = ws_m + nparts * DEC_ROWS;
+    const float* ws_o = p.ws + (part0 * DEC_ROWS + rr) * D;                      // stride DEC_ROWS*D per split
+
+    // pass 1: the maximum over all splits (every thread takes a strided share, then LDS)
     float M = DEC_M_INIT;
-    for (int s = 0; s < p.nsplit; ++s)
-        M = fmaxf(M, ws_m[(part0 + s) * DEC_ROWS + rr]);
+    for (int s = tid; s < p.nsplit; s += MRG_THREADS)
+        M = fmaxf(M, ws_m[(size_t)s * DEC_ROWS]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        M = fmaxf(M, __shfl_xor(M, off));
+    if (lane == 0)
+        red_m[wave] = M;
+    __syncthreads();
+    M = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+
+    // pass 2: weighted sums
     constexpr int EPT = D / 64;  // elements per lane
     float acc[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
         acc[e] = 0.f;
     float L = 0.f;
-    for (int s = 0; s < p.nsplit; ++s) {
-        const float f = __builtin_amdgcn_exp2f(ws_m[(part0 + s) * DEC_ROWS + rr] - M);
-        L += f * ws_l[(part0 + s) * DEC_ROWS + rr];
-        const float* po = p.ws + ((part0 + s) * DEC_ROWS + rr) * D + lane * EPT;
+#pragma unroll 4
+    for (int s = wave; s < p.nsplit; s += MRG_WAVES) {
+        const float f = __builtin_amdgcn_exp2f(ws_m[(size_t)s * DEC_ROWS] - M);
+        L += f * ws_l[(size_t)s * DEC_ROWS];
+        const float* po = ws_o + (size_t)s * DEC_ROWS * D + lane * EPT;
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             acc[e] += f * po[e];
     }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+        red_o[wave][lane * EPT + e] = acc[e];
+    if (lane == 0)
+        red_l[wave] = L;
+    __syncthreads();
+    if (wave != 0)
+        return;
+    L = red_l[0] + red_l[1] + red_l[2] + red_l[3];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+        acc[e] = red_o[0][lane * EPT + e] + red_o[1][lane * EPT + e] + red_o[2][lane * EPT + e] + red_o[3][lane * EPT + e];
     const float inv_l = 1.0f / L;
     // global row index: the R rows of (batch, K/V head) bhk are contiguous in o and lse
     const size_t grow = (size_t)bhk * p.R + r;
@@ -356,7 +395,7 @@ bool make_plan(int B, int Hq, int Hkv, int Sq, int Sk, int D, Plan* pl)
     long long bps = (nblk + nsplit - 1) / nsplit;
     bps = (bps + DEC_WAVES - 1) / DEC_WAVES * DEC_WAVES;
     nsplit = (nblk + bps - 1) / bps;
-    if (nchunks > 65535 || (long long)B * Hkv > 65535 || nsplit > 0x7fffffffLL || nchunks * DEC_ROWS > 0x7fffffffLL)
+    if (nchunks > 65535 || (long long)B * Hkv > 65535 || nsplit > 0x7fffffffLL || R > 0x7fffffffLL)
         return false;
     pl->nchunks = (int)nchunks;
     pl->nsplit = (int)nsplit;
@@ -373,8 +412,8 @@ int launch_decode(const DecodeParams& p, hipStream_t stream)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_launch(e);
-    const dim3 g2((unsigned)(p.nchunks * DEC_ROWS), (unsigned)(p.B * p.Hkv));
-    hipLaunchKernelGGL((naut_decode_merge_kernel<D, DT_OUT>), g2, dim3(64), 0, stream, p);
+    const dim3 g2((unsigned)p.R, (unsigned)(p.B * p.Hkv));
+    hipLaunchKernelGGL((naut_decode_merge_kernel<D, DT_OUT>), g2, dim3(MRG_THREADS), 0, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess)
         return fail_launch(e);
