@@ -80,6 +80,30 @@ int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float
                      int B, int Hq, int Hkv, int S, int D, int causal, float scale, void* stream,
                      int in_dtype, int out_dtype);
 
+/*
+ * Element strides of the batch, head and sequence axes of q, k, v and o (the D axis is contiguous).
+ * [B][H][S][D] has {H*S*D, S*D, D}; [B][S][H][D], the layout most frameworks produce, {S*H*D, D, H*D}.
+ */
+typedef struct {
+    long long q_b, q_h, q_s;
+    long long k_b, k_h, k_s;
+    long long v_b, v_h, v_s;
+    long long o_b, o_h, o_s;
+} naut_strides;
+
+/*
+ * The same operator on strided tensors and on other head dimensions (the paper's evaluation spans
+ * models with "less common" head sizes, Section 7.1): D any multiple of 8 up to 128 -- a narrower
+ * head runs on the 64- or 128-wide kernel with the missing columns of Q read as zero.  `st` gives
+ * element strides as above (NULL = contiguous [B][H][S][D]); q/k/v strides must be non-negative
+ * multiples of 8 (16 bytes; 0 broadcasts a tensor along that axis), o strides positive multiples of 4,
+ * every sequence stride at least D and at most 2^23.  lse stays contiguous [B][Hq][S].  Everything else
+ * as naut_attn_fwd_dt, which is this call with st = NULL and D restricted to 64 or 128.
+ */
+int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, float* lse,
+                          int B, int Hq, int Hkv, int S, int D, int causal, float scale, void* stream,
+                          int in_dtype, int out_dtype, const naut_strides* st);
+
 /* Message for the last non-OK status returned on the calling thread ("" if none). Never NULL. */
 const char* naut_last_error_string(void);
 

@@ -57,6 +57,13 @@ struct Params {
     int nqt;       // number of 128-query tiles = ceil(S / BM)
     int nqt2;      // number of 256-query tiles
     float c;       // scale * log2(e), > 0
+    // Byte strides of batch, head and sequence position (the D axis is contiguous).  The kernels are
+    // compiled for D = 64 or 128; a smaller head dimension runs on the next wider one: cpr 16-byte
+    // chunks of every row are real, the chunks of Q beyond them read as zero, those of K and V repeat
+    // a real chunk (they meet zeros of Q, or end in columns of O that are not stored).
+    long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
+    int q_rs, k_rs, v_rs, o_rs;
+    int cpr;       // real 16-byte chunks per row = head dimension / 8
 };
 
 // ---- kernel 1: 128 queries per work-group, 4 wavefronts x 32 queries, two work-groups per CU ----
@@ -92,9 +99,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel_bm128(const Param
     const int hk = hq / (p.Hq / p.Hkv);
     const int S = p.S;
 
-    const unsigned char* qg = (const unsigned char*)p.q + (size_t)bh * S * ROWB;
-    const unsigned char* kg = (const unsigned char*)p.k + (size_t)(b * p.Hkv + hk) * S * ROWB;
-    const unsigned char* vg = (const unsigned char*)p.v + (size_t)(b * p.Hkv + hk) * S * ROWB;
+    const unsigned char* qg = (const unsigned char*)p.q + b * p.q_bs + hq * p.q_hs;
+    const unsigned char* kg = (const unsigned char*)p.k + b * p.k_bs + hk * p.k_hs;
+    const unsigned char* vg = (const unsigned char*)p.v + b * p.v_bs + hk * p.v_hs;
+    const int cpr = p.cpr;
 
     const int q_wave0 = qt * BM + wave * 32;  // first query of this wavefront
     const int my_q = q_wave0 + l32;           // the query this lane owns
@@ -104,7 +112,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel_bm128(const Param
     i32x4_t qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = *(const i32x4_t*)(qg + (size_t)my_q_ld * ROWB + ks * 32 + h * 16);
+        qf[ks] = ks * 2 + h < cpr ? *(const i32x4_t*)(qg + (size_t)my_q_ld * p.q_rs + ks * 32 + h * 16)
+                                  : i32x4_t{0, 0, 0, 0};
     // Keep Q resident: without this the compiler re-issues the global loads inside the key loop.
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
@@ -121,9 +130,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel_bm128(const Param
             const int L = tid + NTHREADS * i;
             int row = tile * BN + L / CPR;
             row = row < S ? row : S - 1;
-            const size_t off = (size_t)row * ROWB + (L % CPR) * 16;
-            kst[i] = *(const i32x4_t*)(kg + off);
-            vst[i] = *(const i32x4_t*)(vg + off);
+            const int ch = L % CPR < cpr ? L % CPR : cpr - 1;
+            kst[i] = *(const i32x4_t*)(kg + (size_t)row * p.k_rs + ch * 16);
+            vst[i] = *(const i32x4_t*)(vg + (size_t)row * p.v_rs + ch * 16);
         }
     };
     auto s_store = [&](int buf) {
@@ -247,12 +256,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel_bm128(const Param
         if (p.lse != nullptr && h == 0)
             p.lse[(size_t)bh * S + my_q] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
         constexpr int OUTB = DT_OUT == NAUT_F32 ? 4 : 2;
-        unsigned char* og = (unsigned char*)p.o + ((size_t)bh * S + my_q) * D * OUTB;
+        unsigned char* og = (unsigned char*)p.o + b * p.o_bs + hq * p.o_hs + (size_t)my_q * p.o_rs;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int d = 32 * db + 8 * g + 4 * h;
+                if (d >= cpr * 8)
+                    continue;  // padding columns of a narrower head dimension
                 const float x0 = oacc[db][4 * g + 0] * inv_l, x1 = oacc[db][4 * g + 1] * inv_l;
                 const float x2 = oacc[db][4 * g + 2] * inv_l, x3 = oacc[db][4 * g + 3] * inv_l;
                 if constexpr (DT_OUT == NAUT_F32) {
@@ -459,9 +470,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     float c_v = c;  // copy held in a vector register: an FMA with a scalar-register operand issues at the slower rate
     asm volatile("" : "+v"(c_v));
 
-    const unsigned char* qg = (const unsigned char*)p.q + (size_t)bh * S * ROWB;
-    const unsigned char* kg = (const unsigned char*)p.k + (size_t)(b * p.Hkv + hk) * S * ROWB;
-    const unsigned char* vg = (const unsigned char*)p.v + (size_t)(b * p.Hkv + hk) * S * ROWB;
+    const unsigned char* qg = (const unsigned char*)p.q + b * p.q_bs + hq * p.q_hs;
+    const unsigned char* kg = (const unsigned char*)p.k + b * p.k_bs + hk * p.k_hs;
+    const unsigned char* vg = (const unsigned char*)p.v + b * p.v_bs + hk * p.v_hs;
+    const int cpr = p.cpr;
 
     const int Q0 = qt * BM2 + wave * WQ;  // first query of this wavefront
     int qrow[QH];
@@ -476,7 +488,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         const int q_ld = qrow[hf] < S ? qrow[hf] : S - 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            qf[hf][ks] = *(const i32x4_t*)(qg + (size_t)q_ld * ROWB + ks * 32 + h * 16);
+            qf[hf][ks] = ks * 2 + h < cpr ? *(const i32x4_t*)(qg + (size_t)q_ld * p.q_rs + ks * 32 + h * 16)
+                                          : i32x4_t{0, 0, 0, 0};
     }
 #pragma unroll
     for (int hf = 0; hf < QH; ++hf)
@@ -497,20 +510,27 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     // the block, so the lane fetches the logical chunk that the swizzle maps there.  The address is
     // (scalar tile base) + (per-lane constant offset), so a full tile costs no vector arithmetic.
     int k_goff[LD_PER_W], v_goff[LD_PER_W];  // byte offset of the lane's chunk inside a tile
+    int k_grow[LD_PER_W], v_grow[LD_PER_W];  // its row inside the tile (set-up only)
 #pragma unroll
     for (int i = 0; i < LD_PER_W; ++i) {
         const int P = (wave * LD_PER_W + i) * 64 + lane;  // physical chunk index in the tile
         {
             const int line = P >> 4, pos = P & 15;
             const int L = (line << 4) + (pos ^ (line & 15));
-            k_goff[i] = L * 16;  // rows are contiguous in memory: row * ROWB + chunk * 16 == L * 16
+            const int krow = L / (D / 8), kch = L % (D / 8);  // logical chunk L = row krow, chunk kch
+            k_goff[i] = krow * p.k_rs + (kch < cpr ? kch : cpr - 1) * 16;
+            k_grow[i] = krow;
         }
         if constexpr (D == 128) {
             const int row = P >> 4, cc = P & 15;
-            v_goff[i] = row * ROWB + (cc ^ ((row & 3) << 2)) * 16;
+            const int lc = cc ^ ((row & 3) << 2);
+            v_goff[i] = row * p.v_rs + (lc < cpr ? lc : cpr - 1) * 16;
+            v_grow[i] = row;
         } else {
             const int row = P >> 3, cc = P & 7;
-            v_goff[i] = row * ROWB + (cc ^ (((row >> 1) & 1) << 2)) * 16;
+            const int lc = cc ^ (((row >> 1) & 1) << 2);
+            v_goff[i] = row * p.v_rs + (lc < cpr ? lc : cpr - 1) * 16;
+            v_grow[i] = row;
         }
     }
     const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
@@ -523,9 +543,9 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         const int rows_left = S - (ntiles - 1) * BN;  // >= 1
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i) {
-            const int kr = k_goff[i] / ROWB, vr = v_goff[i] / ROWB;
-            k_goff_last[i] = kr < rows_left ? k_goff[i] : (rows_left - 1) * ROWB + k_goff[i] % ROWB;
-            v_goff_last[i] = vr < rows_left ? v_goff[i] : (rows_left - 1) * ROWB + v_goff[i] % ROWB;
+            const int kr = k_grow[i], vr = v_grow[i];
+            k_goff_last[i] = kr < rows_left ? k_goff[i] : k_goff[i] - (kr - (rows_left - 1)) * p.k_rs;
+            v_goff_last[i] = vr < rows_left ? v_goff[i] : v_goff[i] - (vr - (rows_left - 1)) * p.v_rs;
         }
     }
     struct TileLoad {
@@ -533,11 +553,11 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         const unsigned char* gt;  // global address of the tile (wave-uniform)
         bool last;                // the tile is the last one: use the second set of offsets
     };
-    auto tile_load = [&](const unsigned char* g, unsigned lds_tiles, int tile) {
+    auto tile_load = [&](const unsigned char* g, int row_stride, unsigned lds_tiles, int tile) {
         TileLoad t;
         const int tl = tile < ntiles ? tile : ntiles - 1;
         t.dst = lds_tiles + (unsigned)((tile % NBUF) * TILEB + wave * LD_PER_W * 1024);
-        t.gt = g + ((ABL & 128) ? (size_t)0 : (size_t)tl * TILEB);
+        t.gt = g + ((ABL & 128) ? (size_t)0 : (size_t)tl * BN * row_stride);
         t.last = tile >= ntiles - 1;
         return t;
     };
@@ -793,7 +813,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
     for (int t = 0; t < LA; ++t)
     {
-        const TileLoad tk = tile_load(kg, k_lds, t);
+        const TileLoad tk = tile_load(kg, p.k_rs, k_lds, t);
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i)
             issue_load(tk, i, k_goff, k_goff_last);
@@ -801,7 +821,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
     for (int t = 0; t + 1 < LA; ++t)
     {
-        const TileLoad tv = tile_load(vg, v_lds, t);
+        const TileLoad tv = tile_load(vg, p.v_rs, v_lds, t);
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i)
             issue_load(tv, i, v_goff, v_goff_last);
@@ -843,7 +863,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // The 2*LD_PER_W loads of a wavefront are dealt out over the MFMA slots of one stage (even
         // wavefronts: the first stage, odd ones: the second) rather than issued in one burst by all
         // wavefronts right after the barrier, which backs up the memory pipeline and stalls them.
-        const TileLoad kt = tile_load(kg, k_lds, j + LA), vt = tile_load(vg, v_lds, j + LA - 1);
+        const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA), vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1);
         if constexpr (!(ABL & 8) && NAUT_SPREAD == 0) {
 #pragma unroll
             for (int i = 0; i < LD_PER_W; ++i)
@@ -919,12 +939,14 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         const float inv_l = 1.0f / lt;
         if (p.lse != nullptr && h == 0)
             p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
-        unsigned char* og = (unsigned char*)p.o + ((size_t)bh * S + q) * D * OUTB;
+        unsigned char* og = (unsigned char*)p.o + b * p.o_bs + hq * p.o_hs + (size_t)q * p.o_rs;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int d = 32 * db + 8 * g + 4 * h;
+                if (d >= cpr * 8)
+                    continue;  // padding columns of a narrower head dimension
                 const float x0 = oacc[hf][db][4 * g + 0] * inv_l, x1 = oacc[hf][db][4 * g + 1] * inv_l;
                 const float x2 = oacc[hf][db][4 * g + 2] * inv_l, x3 = oacc[hf][db][4 * g + 3] * inv_l;
                 if constexpr (DT_OUT == NAUT_F32) {
@@ -1036,8 +1058,9 @@ bool dtype_pair_ok(int in_dtype, int out_dtype)
 
 extern "C" {
 
-int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
-                     int S, int D, int causal, float scale, void* stream, int in_dtype, int out_dtype)
+int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                          int S, int D, int causal, float scale, void* stream, int in_dtype, int out_dtype,
+                          const naut_strides* st)
 {
     if (!q || !k || !v || !o)
         return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
@@ -1049,8 +1072,8 @@ int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float
         return fail(NAUT_ERR_SHAPE, "scale must be finite");
     if (scale < 0.f)
         return fail(NAUT_ERR_UNSUPPORTED, "negative scale is not supported");
-    if (D != 64 && D != 128)
-        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    if (D % 8 != 0 || D > 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 8, at most 128");
     if (!dtype_pair_ok(in_dtype, out_dtype))
         return fail(NAUT_ERR_UNSUPPORTED, "supported dtypes: q/k/v bf16 or f16; o of the same type or f32");
     if ((long long)B * Hq > 0x7fffffffLL || (long long)B * Hkv > 0x7fffffffLL)
@@ -1060,6 +1083,26 @@ int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float
     if ((uintptr_t)lse & 3u)
         return fail(NAUT_ERR_ALIGN, "lse must be 4-byte aligned");
 
+    naut_strides cs;  // contiguous [B][H][S][D]
+    cs.q_s = cs.k_s = cs.v_s = cs.o_s = D;
+    cs.q_h = cs.o_h = cs.k_h = cs.v_h = (long long)S * D;
+    cs.q_b = cs.o_b = (long long)Hq * S * D;
+    cs.k_b = cs.v_b = (long long)Hkv * S * D;
+    if (!st)
+        st = &cs;
+    const long long in_strides[9] = {st->q_b, st->q_h, st->q_s, st->k_b, st->k_h, st->k_s, st->v_b, st->v_h, st->v_s};
+    for (long long x : in_strides)
+        if (x < 0 || x % 8 != 0)
+            return fail(NAUT_ERR_ALIGN, "q/k/v strides must be non-negative multiples of 8 elements (16 bytes)");
+    if (st->o_b <= 0 || st->o_h <= 0 || st->o_s <= 0 || st->o_b % 4 != 0 || st->o_h % 4 != 0 || st->o_s % 4 != 0)
+        return fail(NAUT_ERR_ALIGN, "o strides must be positive multiples of 4 elements");
+    if (st->q_s < D || st->k_s < D || st->v_s < D || st->o_s < D)
+        return fail(NAUT_ERR_SHAPE, "a sequence stride is smaller than D: rows would overlap");
+    const long long max_rs = 1LL << 23;  // elements: keeps 64 rows of byte offsets inside 32 bits
+    if (st->q_s > max_rs || st->k_s > max_rs || st->v_s > max_rs || st->o_s > max_rs)
+        return fail(NAUT_ERR_UNSUPPORTED, "sequence stride too large");
+
+    const int out_b = out_dtype == NAUT_F32 ? 4 : 2;
     Params p;
     p.q = q;
     p.k = k;
@@ -1076,11 +1119,25 @@ int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float
     // replaced by the smallest useful positive constant so that masked scores (-inf) stay -inf.
     const float c = scale * 1.4426950408889634f;
     p.c = c > 0.f ? c : 1e-30f;
-    hipStream_t st = (hipStream_t)stream;
+    p.q_bs = st->q_b * 2;
+    p.q_hs = st->q_h * 2;
+    p.q_rs = (int)(st->q_s * 2);
+    p.k_bs = st->k_b * 2;
+    p.k_hs = st->k_h * 2;
+    p.k_rs = (int)(st->k_s * 2);
+    p.v_bs = st->v_b * 2;
+    p.v_hs = st->v_h * 2;
+    p.v_rs = (int)(st->v_s * 2);
+    p.o_bs = st->o_b * out_b;
+    p.o_hs = st->o_h * out_b;
+    p.o_rs = (int)(st->o_s * out_b);
+    p.cpr = D / 8;
+    hipStream_t st_ = (hipStream_t)stream;
+    const int DK = D <= 64 ? 64 : 128;  // width the kernel is compiled for
 
 #define NAUT_DISPATCH(DD, IN, OUT)                         \
-    if (D == DD && in_dtype == IN && out_dtype == OUT)    \
-        return launch<DD, IN, OUT>(p, causal, st);
+    if (DK == DD && in_dtype == IN && out_dtype == OUT)   \
+        return launch<DD, IN, OUT>(p, causal, st_);
     NAUT_DISPATCH(128, NAUT_BF16, NAUT_BF16)
     NAUT_DISPATCH(64, NAUT_BF16, NAUT_BF16)
     NAUT_DISPATCH(128, NAUT_BF16, NAUT_F32)
@@ -1091,6 +1148,14 @@ int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float
     NAUT_DISPATCH(64, NAUT_F16, NAUT_F32)
 #undef NAUT_DISPATCH
     return fail(NAUT_ERR_UNSUPPORTED, "no kernel for this (D, dtype) combination");
+}
+
+int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                     int S, int D, int causal, float scale, void* stream, int in_dtype, int out_dtype)
+{
+    if (D > 0 && D != 64 && D != 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128 (naut_attn_fwd_strided takes other head dimensions)");
+    return naut_attn_fwd_strided(q, k, v, o, lse, B, Hq, Hkv, S, D, causal, scale, stream, in_dtype, out_dtype, nullptr);
 }
 
 int naut_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int S,

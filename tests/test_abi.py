@@ -118,3 +118,26 @@ def test_decode_argument_checks():
     assert dec(wsp=None) == nb.NAUT_ERR_SHAPE
     assert dec(wsb=ws - 1) == nb.NAUT_ERR_SHAPE
     assert "workspace" in nb.last_error_string()
+
+
+def test_strided_argument_checks():
+    bf = nb.NAUT_BF16
+    D = 96
+    base = dict(q=A, k=A, v=A, o=A, lse=A, B=1, Hq=2, Hkv=2, S=128, D=D, causal=1, scale=0.1)
+
+    def call_s(strides, **kw):
+        a = dict(base)
+        a.update(kw)
+        return nb.naut_attn_fwd_strided_raw(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["Hq"], a["Hkv"], a["S"],
+                                            a["D"], a["causal"], a["scale"], None, bf, bf, strides)
+    bshd = lambda H, S, D: (S * H * D, D, H * D)
+    good = bshd(2, 128, D) * 4
+    assert call_s(good, D=100) == nb.NAUT_ERR_UNSUPPORTED     # not a multiple of 8
+    assert call_s(good, D=136) == nb.NAUT_ERR_UNSUPPORTED     # wider than the widest kernel
+    assert call_s((good[0], good[1], good[2] + 4) + good[3:]) == nb.NAUT_ERR_ALIGN    # q rows not 16-byte aligned
+    assert call_s(good[:9] + (good[9], good[10], 0)) == nb.NAUT_ERR_ALIGN             # o rows would coincide
+    assert call_s(good[:5] + (D - 8,) + good[6:]) == nb.NAUT_ERR_SHAPE                # k rows overlap
+    assert call_s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED        # v row stride too large
+    assert call_s(good, q=None) == nb.NAUT_ERR_NULL
+    # the dense entry points keep their contract: only 64 and 128
+    assert call(D=96) == nb.NAUT_ERR_UNSUPPORTED
