@@ -52,6 +52,13 @@ def _bind(path: str):
     lib.naut_oracle_attn_cross16.restype = ctypes.c_int
     lib.naut_oracle_attn_cross16.argtypes = ([u16p, u16p, u16p, ctypes.c_int, dp, dp] + [ctypes.c_int] * 7
                                              + [ctypes.c_double])
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    lib.naut_oracle_decode_e4m3.restype = ctypes.c_int
+    lib.naut_oracle_decode_e4m3.argtypes = [u8p, dp, ctypes.c_int64]
+    lib.naut_oracle_attn_rows_e4m3.restype = ctypes.c_int
+    lib.naut_oracle_attn_rows_e4m3.argtypes = ([u8p, u8p, u8p, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                                i64p, ctypes.c_int64, dp, dp] + [ctypes.c_int] * 6
+                                               + [ctypes.c_double])
     lib.naut_oracle_decode16.restype = ctypes.c_int
     lib.naut_oracle_decode16.argtypes = [u16p, ctypes.c_int, dp, ctypes.c_int64]
     lib.naut_oracle_threads.restype = ctypes.c_int
@@ -167,3 +174,40 @@ def decode16(bits, dtype: int):
     if rc != 0:
         raise RuntimeError("naut_oracle_decode16 failed: %d" % rc)
     return out
+
+
+def decode_e4m3(bits):
+    """Exact decode of OCP FP8 E4M3 bytes to fp64 (0x7f and 0xff are NaN)."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    out = np.empty(bits.shape, dtype=np.float64)
+    rc = _load().naut_oracle_decode_e4m3(bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), _dptr(out), bits.size)
+    if rc != 0:
+        raise RuntimeError("naut_oracle_decode_e4m3 failed: %d" % rc)
+    return out
+
+
+def attn_rows_e4m3(q_bits, k_bits, v_bits, dq: float, dk: float, dv: float, causal: bool, scale: float, rows=None):
+    """Attention on FP8 E4M3 bytes with per-tensor scales (real tensor = scale * decoded) for selected rows.
+
+    Same conventions as attn_rows."""
+    q = np.ascontiguousarray(q_bits, dtype=np.uint8)
+    k = np.ascontiguousarray(k_bits, dtype=np.uint8)
+    v = np.ascontiguousarray(v_bits, dtype=np.uint8)
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, S, D) and v.shape == k.shape
+    u8 = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    if rows is None:
+        n, rp = B * Hq * S, None
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        n, rp = rows.size, rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    o = np.empty((n, D), dtype=np.float64)
+    lse = np.empty((n,), dtype=np.float64)
+    rc = _load().naut_oracle_attn_rows_e4m3(u8(q), u8(k), u8(v), float(dq), float(dk), float(dv), rp, n, _dptr(o),
+                                            _dptr(lse), B, Hq, Hkv, S, D, int(bool(causal)), float(scale))
+    if rc != 0:
+        raise RuntimeError("naut_oracle_attn_rows_e4m3 failed: %d" % rc)
+    if rows is None:
+        return o.reshape(B, Hq, S, D), lse.reshape(B, Hq, S)
+    return o, lse

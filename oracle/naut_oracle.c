@@ -321,6 +321,107 @@ int naut_oracle_attn_cross16(const uint16_t *q, const uint16_t *k, const uint16_
     return rc;
 }
 
+/* ---- FP8 (OCP E4M3) inputs ----------------------------------------------------- */
+
+/*
+ * OCP FP8 E4M3 ("e4m3fn"), the second input precision of the paper's experiments (Section 6): 1 sign,
+ * 4 exponent bits (bias 7), 3 fraction bits; no infinities; exponent 15 with fraction 7 is NaN, every
+ * other code is finite (largest 448); exponent 0 is subnormal with steps of 2^-9.
+ */
+static double decode_e4m3(uint8_t bits)
+{
+    const int sign = (bits >> 7) & 1;
+    const int expo = (bits >> 3) & 0xf;
+    const int frac = bits & 7;
+    double mag;
+    if (expo == 15 && frac == 7)
+        mag = NAN;
+    else if (expo == 0)
+        mag = ldexp((double)frac, -9);
+    else
+        mag = ldexp(1.0 + (double)frac / 8.0, expo - 7);
+    return sign ? -mag : mag;
+}
+
+int naut_oracle_decode_e4m3(const uint8_t *bits, double *out, int64_t n)
+{
+    if (!bits || !out || n < 0)
+        return -1;
+    for (int64_t t = 0; t < n; ++t)
+        out[t] = decode_e4m3(bits[t]);
+    return 0;
+}
+
+/*
+ * Self-attention for a chosen list of query rows on FP8 inputs with per-tensor scales: the real
+ * tensors are dq * decode(q), dk * decode(k), dv * decode(v) and the operator is the one above on
+ * those real tensors.  Layouts and `rows` as in naut_oracle_attn_rows.  Pinned by the exhaustive
+ * decode table against an independent library decode and by equality with the fp64 entry point on
+ * the decoded, scaled inputs.
+ */
+int naut_oracle_attn_rows_e4m3(const uint8_t *q, const uint8_t *k, const uint8_t *v, double dq, double dk,
+                               double dv, const int64_t *rows, int64_t nrows, double *o, double *lse, int B,
+                               int Hq, int Hkv, int S, int D, int causal, double scale)
+{
+    if (!q || !k || !v || !o || bad_shape(B, Hq, Hkv, S, D) || nrows < 0)
+        return -1;
+    const int64_t total = (int64_t)B * Hq * S;
+    if (!rows && nrows != total)
+        return -1;
+    if (rows)
+        for (int64_t t = 0; t < nrows; ++t)
+            if (rows[t] < 0 || rows[t] >= total)
+                return -1;
+    const int64_t nkv = (int64_t)B * Hkv * S * D;
+    double *K64 = (double *)malloc(sizeof(double) * (size_t)nkv);
+    double *V64 = (double *)malloc(sizeof(double) * (size_t)nkv);
+    if (!K64 || !V64) {
+        free(K64);
+        free(V64);
+        return -2;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < nkv; ++t) {
+        K64[t] = dk * decode_e4m3(k[t]);
+        V64[t] = dv * decode_e4m3(v[t]);
+    }
+    const int g = Hq / Hkv;
+    int err = 0;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)S);
+        double *q64 = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!s || !q64) {
+#pragma omp atomic write
+            err = -2;
+        }
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t t = 0; t < nrows; ++t) {
+            if (!s || !q64)
+                continue;
+            const int64_t r = rows ? rows[t] : t;
+            const int64_t i = r % S;
+            const int64_t h = (r / S) % Hq;
+            const int64_t b = r / ((int64_t)S * Hq);
+            const int64_t hk = h / g;
+            const int64_t nkeys = causal ? i + 1 : S;
+            for (int d = 0; d < D; ++d)
+                q64[d] = dq * decode_e4m3(q[r * D + d]);
+            const double *Kh = K64 + (b * Hkv + hk) * (int64_t)S * D;
+            const double *Vh = V64 + (b * Hkv + hk) * (int64_t)S * D;
+            double lse_r;
+            attn_row(q64, Kh, Vh, nkeys, D, scale, s, o + t * D, &lse_r);
+            if (lse)
+                lse[t] = lse_r;
+        }
+        free(s);
+        free(q64);
+    }
+    free(K64);
+    free(V64);
+    return err;
+}
+
 /* Exact decode of n 16-bit patterns to fp64 (exposed so tests can pin the decoders). */
 int naut_oracle_decode16(const uint16_t *bits, int dtype, double *out, int64_t n)
 {

@@ -103,6 +103,9 @@ def _load():
                                                 ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int]
         lib.naut_synth_round16.restype = ctypes.c_int
         lib.naut_synth_round16.argtypes = [ctypes.POINTER(ctypes.c_float), u16p, ctypes.c_int64, ctypes.c_int]
+        lib.naut_synth_round_e4m3.restype = ctypes.c_int
+        lib.naut_synth_round_e4m3.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint8),
+                                              ctypes.c_int64]
         _lib = lib
     return _lib
 
@@ -150,3 +153,23 @@ def make_inputs(w: Workload, seed: int | None = None):
     k = fill(w.B, w.Hkv, w.S, w.D, seed, TAG_K, w.in_dtype, w.n_outlier, w.outlier_scale)
     v = fill(w.B, w.Hkv, w.S, w.D, seed, TAG_V, w.in_dtype)
     return q, k, v
+
+
+def round_e4m3(x: np.ndarray) -> np.ndarray:
+    """float32 -> OCP FP8 E4M3 bytes (nearest even, saturating at +-448)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint8)
+    rc = _load().naut_synth_round_e4m3(x.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                       out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), x.size)
+    if rc != 0:
+        raise RuntimeError("naut_synth_round_e4m3 failed: %d" % rc)
+    return out
+
+
+def fill_e4m3(B: int, H: int, S: int, D: int, seed: int, tag: int, descale: float,
+              n_outlier: int = 0, outlier_scale: float = 1.0) -> np.ndarray:
+    """uint8 array [B,H,S,D]: the N(0,1) samples of `fill` (with its outlier rows) divided by `descale` and
+    stored as FP8 E4M3; the tensor's real values are descale * decoded."""
+    bits = fill(B, H, S, D, seed, tag, BF16, n_outlier, outlier_scale)
+    x = (bits.astype(np.uint32) << 16).view(np.float32)
+    return round_e4m3(x / np.float32(descale))

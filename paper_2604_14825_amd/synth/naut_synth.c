@@ -198,3 +198,38 @@ int naut_synth_round16(const float *in, uint16_t *out, int64_t n, int dtype)
         out[t] = round16(in[t], dtype);
     return 0;
 }
+
+/*
+ * Round n floats to OCP FP8 E4M3 ("e4m3fn": 1 sign, 4 exponent bits with bias 7, 3 fraction bits, no
+ * infinities, largest finite value 448), to nearest with ties to even, magnitudes beyond 448 saturating
+ * to 448.  Inputs must be finite.  Used to store the synthetic Q, K, V of the FP8 workloads.
+ */
+int naut_synth_round_e4m3(const float *in, uint8_t *out, int64_t n)
+{
+    if (!in || !out || n < 0)
+        return -1;
+    for (int64_t t = 0; t < n; ++t) {
+        const float x = in[t];
+        const uint8_t sign = signbit(x) ? 0x80 : 0x00;
+        const float a = fabsf(x);
+        uint8_t code;
+        if (!(a < 464.0f)) {          /* 464 is the midpoint between 448 and the first value not representable */
+            code = 0x7e;
+        } else if (a < 0.015625f) {   /* below 2^-6: subnormal steps of 2^-9 (8 steps reach the first normal code) */
+            code = (uint8_t)rintf(a * 512.0f);
+        } else {
+            int e;
+            (void)frexpf(a, &e);      /* a = f * 2^e, f in [0.5, 1)  ->  a = (1 + m/8) * 2^(e-1) */
+            int E = e - 1;
+            int m = (int)rintf(ldexpf(a, -E) * 8.0f) - 8;
+            if (m == 8) {
+                m = 0;
+                E += 1;
+            }
+            const int c = ((E + 7) << 3) | m;
+            code = (uint8_t)(c > 0x7e ? 0x7e : c);
+        }
+        out[t] = sign | code;
+    }
+    return 0;
+}

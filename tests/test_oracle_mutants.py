@@ -31,6 +31,10 @@ MUTANTS = {
     "cross_causal_drops_diagonal": ("causal ? (int64_t)Sk - Sq + i + 1 : Sk", "causal ? (int64_t)Sk - Sq + i + (i > 0 || Sk > Sq ? 0 : 1) : Sk"),
     "cross_kv_head_stride_uses_Sq": ("const double *Kh = k + (b * Hkv + hk) * (int64_t)Sk * D;", "const double *Kh = k + (b * Hkv + hk) * (int64_t)Sq * D;"),
     "cross_row_split_uses_Sk": ("const int64_t h = (r / Sq) % Hq;", "const int64_t h = (r / Sk) % Hq;"),
+    "e4m3_bias_8": ("ldexp(1.0 + (double)frac / 8.0, expo - 7)", "ldexp(1.0 + (double)frac / 8.0, expo - 8)"),
+    "e4m3_subnormal_step": ("mag = ldexp((double)frac, -9);", "mag = ldexp((double)frac, -10);"),
+    "e4m3_four_fraction_bits": ("const int frac = bits & 7;", "const int frac = bits & 15;"),
+    "e4m3_scales_swapped": ("V64[t] = dv * decode_e4m3(v[t]);", "V64[t] = dk * decode_e4m3(v[t]);"),
     "cross16_decodes_V_from_K": ("V64[t] = decode16(v[t], in_dtype);\n        }\n        rc =", "V64[t] = decode16(k[t], in_dtype);\n        }\n        rc ="),
 }
 
@@ -66,6 +70,9 @@ def run_pins():
     pins.test_cross_closed_forms_and_gqa()
     for dt in (oracle.BF16, oracle.F16):
         pins.test_cross16_matches_f64_entry(dt)
+    pins.test_e4m3_decoder_exact_all_codes()
+    for causal in (False, True):
+        pins.test_e4m3_rows_entry_matches_f64_entry(causal)
 
 
 def test_unmutated_copy_passes(tmp_path, monkeypatch):

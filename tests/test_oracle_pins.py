@@ -424,3 +424,36 @@ def test_cross_bad_arguments_rejected():
     with pytest.raises(RuntimeError):
         oracle.attn_cross_f64(q, k, v, True, 1.0)   # causal needs Sk >= Sq
     oracle.attn_cross_f64(q, k, v, False, 1.0)      # fine without the mask
+
+
+# ---------------------------------------------------------------------------
+# FP8 (OCP E4M3) inputs, the paper's second precision (Section 6)
+# ---------------------------------------------------------------------------
+
+def test_e4m3_decoder_exact_all_codes():
+    import torch  # an independent, library decode of all 256 codes (CPU)
+    codes = np.arange(256, dtype=np.uint8)
+    want = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    got = oracle.decode_e4m3(codes)
+    assert np.isnan(got[[0x7F, 0xFF]]).all() and np.isnan(want[[0x7F, 0xFF]]).all()
+    ok = ~np.isnan(want)
+    np.testing.assert_array_equal(got[ok], want[ok])
+    assert got[0x7E] == 448.0 and got[0x38] == 1.0 and got[0x01] == 2.0 ** -9 and got[0xC6] == -3.5
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_e4m3_rows_entry_matches_f64_entry(causal):
+    g = rng(41)
+    B, Hq, Hkv, S, D = 2, 4, 2, 19, 8
+    bits = lambda shape: (g.integers(0, 0x7F, shape).astype(np.uint8) | (g.integers(0, 2, shape).astype(np.uint8) << 7))
+    q, k, v = bits((B, Hq, S, D)), bits((B, Hkv, S, D)), bits((B, Hkv, S, D))
+    dq, dk, dv = 1 / 64, 1 / 8, 1 / 32
+    o1, l1 = oracle.attn_rows_e4m3(q, k, v, dq, dk, dv, causal, 0.35)
+    o2, l2 = oracle.attn_f64(dq * oracle.decode_e4m3(q), dk * oracle.decode_e4m3(k), dv * oracle.decode_e4m3(v),
+                             causal, 0.35)
+    np.testing.assert_array_equal(o1, o2)
+    np.testing.assert_array_equal(l1, l2)
+    rows = np.array([0, 5, B * Hq * S - 1], dtype=np.int64)
+    o3, l3 = oracle.attn_rows_e4m3(q, k, v, dq, dk, dv, causal, 0.35, rows=rows)
+    np.testing.assert_array_equal(o3, o2.reshape(-1, D)[rows])
+    np.testing.assert_array_equal(l3, l2.reshape(-1)[rows])

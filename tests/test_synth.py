@@ -84,3 +84,28 @@ def test_workload_table_matches_declared_shapes():
     assert abs(w["long"].io_bytes - 539e6) / 539e6 < 5e-3
     q, k, v = synth.make_inputs(w["tiny"])
     assert q.shape == (1, 2, 256, 64) and k.shape == q.shape and q.dtype == np.uint16
+
+
+def test_round_e4m3_matches_library_rounding():
+    """Nearest-even rounding to FP8 E4M3 against PyTorch's CPU conversion on every in-range float16 value
+    (all exactly representable in float32) and on random float32 values; saturation beyond 448."""
+    import torch
+    vals = np.arange(0, 1 << 16, dtype=np.uint16).view(np.float16).astype(np.float32)
+    vals = vals[np.isfinite(vals) & (np.abs(vals) <= 448.0)]
+    g = np.random.default_rng(3)
+    vals = np.concatenate([vals, (g.standard_normal(20000) * 40).astype(np.float32),
+                           (g.standard_normal(20000) * 0.01).astype(np.float32)])
+    vals = vals[np.abs(vals) <= 448.0]
+    got = synth.round_e4m3(vals)
+    want = torch.from_numpy(vals.copy()).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(got, want)
+    big = np.array([449.0, 464.0, 465.0, 1e4, -1e30], dtype=np.float32)
+    np.testing.assert_array_equal(synth.round_e4m3(big), np.array([0x7E, 0x7E, 0x7E, 0x7E, 0xFE], dtype=np.uint8))
+
+
+def test_fill_e4m3_is_the_scaled_rounded_fill():
+    a = synth.fill_e4m3(1, 2, 50, 16, 11, synth.TAG_K, 0.125, 2, 8.0)
+    b16 = synth.fill(1, 2, 50, 16, 11, synth.TAG_K, synth.BF16, 2, 8.0)
+    x = (b16.astype(np.uint32) << 16).view(np.float32) / np.float32(0.125)
+    np.testing.assert_array_equal(a, synth.round_e4m3(x))
+    assert a.dtype == np.uint8 and a.shape == (1, 2, 50, 16)
