@@ -104,6 +104,19 @@ int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, 
                           int B, int Hq, int Hkv, int S, int D, int causal, float scale, void* stream,
                           int in_dtype, int out_dtype, const naut_strides* st);
 
+/*
+ * The same operator on FP8 inputs, the second precision of the paper's experiments (Section 6): q, k, v
+ * are OCP E4M3 bytes (1 sign, 4 exponent bits with bias 7, 3 fraction bits; 0x7f/0xff are NaN and must not
+ * occur), contiguous [B][H][S][D] like the 16-bit entry points, each with one scale per tensor: the real
+ * tensors are descale_q * q, descale_k * k, descale_v * v (all descale factors > 0).  o is bf16, lse fp32.
+ * Both products run on the FP8 matrix instructions with fp32 accumulation; P is rounded to E4M3 for the
+ * second product (that rounding, relative 2^-4, is what the accuracy of this entry point is bound by).
+ * D is 64 or 128.  Everything else as naut_attn_fwd.
+ */
+int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse,
+                      int B, int Hq, int Hkv, int S, int D, int causal, float scale,
+                      float descale_q, float descale_k, float descale_v, void* stream);
+
 /* Message for the last non-OK status returned on the calling thread ("" if none). Never NULL. */
 const char* naut_last_error_string(void);
 

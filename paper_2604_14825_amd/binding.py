@@ -25,7 +25,7 @@ NAUT_F32 = 2
 
 EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
            "naut_attn_variant_name", "naut_attn_decode", "naut_attn_decode_dt", "naut_attn_decode_workspace_bytes",
-           "naut_attn_fwd_strided")
+           "naut_attn_fwd_strided", "naut_attn_fwd_fp8")
 
 
 class NautStrides(ctypes.Structure):
@@ -65,6 +65,8 @@ def lib():
         L.naut_attn_fwd_strided.restype = ci
         L.naut_attn_fwd_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, ci, ci,
                                             ctypes.POINTER(NautStrides)]
+        L.naut_attn_fwd_fp8.restype = ci
+        L.naut_attn_fwd_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp]
         sz = ctypes.c_size_t
         L.naut_attn_decode.restype = ci
         L.naut_attn_decode.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
@@ -224,5 +226,39 @@ def naut_attn_fwd_strided(q, k, v, o, lse, causal: bool, scale: float, stream=No
     st = NautStrides(*[t.stride(a) for t in (q, k, v, o) for a in (0, 1, 2)])
     rc = naut_attn_fwd_strided_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, S, D,
                                    causal, scale, stream.cuda_stream, _torch_dtype_code(q), _torch_dtype_code(o), st)
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())
+
+
+def naut_attn_fwd_fp8_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, S, D, causal, scale, dq, dk, dv,
+                          stream_ptr) -> int:
+    """Direct call with integer device addresses; returns the status code."""
+    return int(lib().naut_attn_fwd_fp8(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, S, D, int(causal), float(scale),
+                                       float(dq), float(dk), float(dv), stream_ptr))
+
+
+def naut_attn_fwd_fp8(q, k, v, o, lse, causal: bool, scale: float, descale_q: float, descale_k: float,
+                      descale_v: float, stream=None):
+    """Attention forward on FP8 E4M3 inputs: q,k,v uint8 (or float8_e4m3fn) device tensors [B,H,S,D], contiguous;
+    o bf16 [B,Hq,S,D]; lse fp32 [B,Hq,S] or None; real tensors are descale_* times the decoded bytes."""
+    import torch
+    for t in (q, k, v, o):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("q, k, v, o must be contiguous device tensors")
+    if any(t.element_size() != 1 for t in (q, k, v)) or o.dtype != torch.bfloat16:
+        raise ValueError("q, k, v must be 1-byte tensors (E4M3) and o bf16")
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    if tuple(k.shape) != (B, Hkv, S, D) or tuple(v.shape) != (B, Hkv, S, D) or tuple(o.shape) != (B, Hq, S, D):
+        raise ValueError("shape mismatch between q, k, v, o")
+    lse_ptr = None
+    if lse is not None:
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, Hq, S)):
+            raise ValueError("lse must be a contiguous fp32 device tensor [B,Hq,S]")
+        lse_ptr = lse.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    rc = naut_attn_fwd_fp8_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, S, D, causal,
+                               scale, descale_q, descale_k, descale_v, stream.cuda_stream)
     if rc != NAUT_OK:
         raise NautError(rc, last_error_string())

@@ -7,7 +7,7 @@ import sys
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SRCS = [os.path.join(_HERE, "csrc", n) for n in ("naut_attn.hip", "naut_decode.hip")]
+SRCS = [os.path.join(_HERE, "csrc", n) for n in ("naut_attn.hip", "naut_decode.hip", "naut_fp8.hip")]
 LIB = os.path.join(_HERE, "libnaut_attn.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

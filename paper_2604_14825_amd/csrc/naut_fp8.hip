@@ -1,0 +1,349 @@
+// naut_fp8.hip -- fused attention forward on FP8 (OCP E4M3) inputs for gfx950 (MI355X).
+//
+// The second precision of the paper's experiments (Section 6: every workload is run in FP16 and FP8).
+// Q, K and V are E4M3 bytes with one scale per tensor (real value = descale * decoded); both matrix
+// products run on the 32x32x64 FP8 MFMA with fp32 accumulation, the softmax in fp32, O is written as
+// bf16.  Same formulation as the 16-bit kernels: scores are held transposed (S^T = K.Q^T, a lane owns
+// one query), the online softmax keeps a lazily moved reference maximum, and P, converted to E4M3, is
+// used straight from the score registers as the B operand of O^T += V^T.P^T.
+//
+// What is specific to 8-bit operands (layouts verified with a probe on the device):
+//   - the MFMA takes 32 consecutive k-values per lane: lane l holds row l%32, k = 32*(l/32) .. +31;
+//   - one instruction covers 64 keys of P.V, so the key axis is processed 64 keys (two 32-key score
+//     blocks) at a time, and k-slot 16*blk + r of a lane half stands for the key of score register r of
+//     block blk -- P needs no shuffle, its 32 bytes are the two blocks' registers in order;
+//   - V^T fragments come from ds_read_b64_tr_b8: within 16 lanes, lane i supplies the address of 8
+//     bytes X_i, lane j < 8 receives byte j of X_0, X_2, .., X_14 and lane 8+j byte j of X_1, X_3, ..,
+//     X_15.  With X_2e = V[key_e][d0 .. d0+7] and X_2e+1 = V[key_e][d0+8 .. d0+15] a group of 16 lanes
+//     gets, for 16 consecutive d, the same 8 keys each;
+//   - P is scaled by 2^7 before the conversion (E4M3 has 3 fraction bits and loses everything below
+//     2^-9): with the reference maximum at most one binade below the true one P*2^7 <= 256 < 448, and
+//     the factor cancels in O / l.  The conversion does not saturate (it makes NaN), hence the bound.
+//
+// Work decomposition as the 128-query kernel of naut_attn.hip: 4 wavefronts x 32 queries per
+// work-group, 64-key tiles, register-staged loads, double-buffered LDS, one barrier per tile.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+
+#include "naut_attn.h"
+#include "naut_common.h"
+
+namespace {
+
+using namespace naut;
+
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
+
+constexpr int F8_BM = 128;
+constexpr int F8_BN = 64;
+constexpr int F8_WAVES = 4;
+constexpr int F8_THREADS = F8_WAVES * 64;
+constexpr float F8_TAU = 1.0f;      // the reference maximum moves when a row exceeds it by more than 2^1
+constexpr float F8_P_SHIFT = 7.0f;  // P is formed as exp2(.. + 7): <= 2^(1+7) = 256, inside E4M3's range
+constexpr float F8_M_INIT = -1.0e30f;
+
+struct Fp8Params {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    float* lse;
+    int B, Hq, Hkv, S;
+    int nqt;        // ceil(S / 128)
+    float c;        // scale * descale_q * descale_k * log2(e), > 0
+    float dv;       // descale_v
+};
+
+// K tile: 64 rows of D bytes; 16-byte chunks of a row XOR-ed with (row/2) so that the 32 lanes that read
+// the same chunk of 32 consecutive rows cover all banks.
+template <int D>
+__device__ __forceinline__ int k8_off(int row, int c16)
+{
+    constexpr int CPR = D / 16;
+    return row * D + ((c16 ^ ((row >> 1) & (CPR - 1))) << 4);
+}
+// V tile: 32-byte chunks of a row XOR-ed with (row/2): the 16 rows x 32 bytes of one transposed read
+// then touch every bank twice, the minimum for 512 bytes.
+template <int D>
+__device__ __forceinline__ int v8_off(int row, int c32)
+{
+    constexpr int CPR = D / 32;
+    return row * D + ((c32 ^ ((row >> 1) & (CPR - 1))) << 5);
+}
+
+__device__ __forceinline__ int pack4_fp8(float x0, float x1, float x2, float x3)
+{
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+    return __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, w, true);
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Params p)
+{
+    constexpr int TILEB = F8_BN * D;            // bytes per K or V tile
+    constexpr int CPR16 = D / 16;               // 16-byte chunks per row
+    constexpr int LD_PER_T = F8_BN * CPR16 / F8_THREADS;
+    constexpr int KS = D / 64;                  // MFMA k-steps of Q.K^T (64 d-values each)
+    constexpr int DB = D / 32;                  // 32-row blocks of O^T
+    static_assert(LD_PER_T >= 1, "every thread stages at least one chunk");
+
+    __shared__ __attribute__((aligned(256))) unsigned char smem[4 * TILEB];  // K0 V0 K1 V1
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+
+    const int nbh = p.B * p.Hq;
+    const int bid = blockIdx.x;
+    const int qt = p.nqt - 1 - bid / nbh;  // heaviest query tiles first
+    const int bh = bid % nbh;
+    const int b = bh / p.Hq;
+    const int hq = bh % p.Hq;
+    const int hk = hq / (p.Hq / p.Hkv);
+    const int S = p.S;
+    const float c = p.c;
+
+    const unsigned char* qg = (const unsigned char*)p.q + (size_t)bh * S * D;
+    const unsigned char* kg = (const unsigned char*)p.k + (size_t)(b * p.Hkv + hk) * S * D;
+    const unsigned char* vg = (const unsigned char*)p.v + (size_t)(b * p.Hkv + hk) * S * D;
+
+    const int q_wave0 = qt * F8_BM + wave * 32;
+    const int my_q = q_wave0 + l32;
+    const int my_q_ld = my_q < S ? my_q : S - 1;
+
+    // Q^T fragments (MFMA B operand): lane holds q[my_q][64*ks + 32*h .. +32]
+    i32x8_t qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const i32x4_t lo = *(const i32x4_t*)(qg + (size_t)my_q_ld * D + ks * 64 + h * 32);
+        const i32x4_t hi = *(const i32x4_t*)(qg + (size_t)my_q_ld * D + ks * 64 + h * 32 + 16);
+        qf[ks] = i32x8_t{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        asm volatile("" : "+v"(qf[ks]));
+
+    const int kv_end = CAUSAL ? (S < (qt + 1) * F8_BM ? S : (qt + 1) * F8_BM) : S;
+    const int ntiles = (kv_end + F8_BN - 1) / F8_BN;
+
+    i32x4_t kst[LD_PER_T], vst[LD_PER_T];
+    auto g_load = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < LD_PER_T; ++i) {
+            const int L = tid + F8_THREADS * i;
+            int row = tile * F8_BN + L / CPR16;
+            row = row < S ? row : S - 1;
+            const size_t off = (size_t)row * D + (L % CPR16) * 16;
+            kst[i] = *(const i32x4_t*)(kg + off);
+            vst[i] = *(const i32x4_t*)(vg + off);
+        }
+    };
+    auto s_store = [&](int buf) {
+        unsigned char* kt = smem + buf * 2 * TILEB;
+        unsigned char* vt = kt + TILEB;
+#pragma unroll
+        for (int i = 0; i < LD_PER_T; ++i) {
+            const int L = tid + F8_THREADS * i;
+            const int row = L / CPR16, c16 = L % CPR16;
+            *(i32x4_t*)(kt + k8_off<D>(row, c16)) = kst[i];
+            *(i32x4_t*)(vt + v8_off<D>(row, c16 >> 1) + (c16 & 1) * 16) = vst[i];
+        }
+    };
+
+    // lane-constant parts of the transposed V reads (see the file header): key index e and byte offset
+    const int i16 = lane & 15;
+    const int v_e = i16 >> 1;                                      // which of the 8 keys of a read this lane addresses
+    const int v_key = 4 * h + (v_e & 3) + ((v_e >> 2) << 3);       // + base(t): keys {0,1,2,3,8,9,10,11} + 4h
+    const int v_byte = 16 * ((lane >> 4) & 1) + 8 * (i16 & 1);     // inside the 32-byte chunk of block db
+
+    f32x16_t oacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            oacc[db][r] = 0.f;
+    float m_run = F8_M_INIT;
+    float l_run = 0.f;
+
+    g_load(0);
+    s_store(0);
+    __syncthreads();
+
+    for (int j = 0; j < ntiles; ++j) {
+        const int buf = j & 1;
+        const unsigned char* kt = smem + buf * 2 * TILEB;
+        const unsigned char* vt = kt + TILEB;
+        const int kv0 = j * F8_BN;
+        if (j + 1 < ntiles)
+            g_load(j + 1);
+
+        const bool active = !CAUSAL || kv0 <= q_wave0 + 31;
+        if (active) {
+            f32x16_t sacc[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    sacc[kb][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int row = kb * 32 + l32, c0 = ks * 4 + h * 2;
+                    const i32x4_t lo = *(const i32x4_t*)(kt + k8_off<D>(row, c0));
+                    const i32x4_t hi = *(const i32x4_t*)(kt + k8_off<D>(row, c0 + 1));
+                    const i32x8_t kf = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    sacc[kb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[ks], sacc[kb], 0, 0, 0, 0, 0, 0);
+                }
+            }
+            const bool need_mask = (CAUSAL && kv0 + F8_BN - 1 > q_wave0) || (kv0 + F8_BN > S);
+            if (need_mask) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = kv0 + kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                        const bool dead = (CAUSAL && key > my_q) || key >= S;
+                        sacc[kb][r] = dead ? -INFINITY : sacc[kb][r];
+                    }
+            }
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    mx = fmaxf(mx, sacc[kb][r]);
+            mx = half_max(mx);
+            const float m_cand = mx * c;
+            if (__builtin_amdgcn_ballot_w64(m_cand > m_run + F8_TAU) != 0) {
+                const float m_new = fmaxf(m_run, m_cand);
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // repair factor
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        oacc[db][r] *= alpha;
+            }
+            const float shift = F8_P_SHIFT - m_run;
+            float psum = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, shift));
+                    sacc[kb][r] = pv;
+                    psum += pv;
+                }
+            l_run += psum;
+            // P as the B operand: k-slot 16*kb + r of this lane half is score register r of block kb
+            i32x8_t pb;
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+                const int kb = w >> 2, r0 = (w & 3) * 4;
+                pb[w] = pack4_fp8(sacc[kb][r0 + 0], sacc[kb][r0 + 1], sacc[kb][r0 + 2], sacc[kb][r0 + 3]);
+            }
+            // O^T += V^T . P^T, all 64 keys of the tile in one MFMA per 32 rows of O^T
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                i32x8_t vf;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int key = 32 * (t >> 1) + 16 * (t & 1) + v_key;
+                    const i32x2_t x = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                        (NAUT_LDS i32x2_t*)(vt + v8_off<D>(key, db) + v_byte));
+                    vf[2 * t] = x.x;
+                    vf[2 * t + 1] = x.y;
+                }
+                oacc[db] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pb, oacc[db], 0, 0, 0, 0, 0, 0);
+            }
+        }
+        if (j + 1 < ntiles)
+            s_store(buf ^ 1);
+        __syncthreads();
+    }
+
+    // Epilogue: one division by l (the 2^7 of P cancels), times descale_v; lse undoes the shift.
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv_l = p.dv / l_tot;
+    if (my_q < S) {
+        if (p.lse != nullptr && h == 0)
+            p.lse[(size_t)bh * S + my_q] = (m_run - F8_P_SHIFT + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+        unsigned char* og = (unsigned char*)p.o + ((size_t)bh * S + my_q) * D * 2;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int d = 32 * db + 8 * g + 4 * h;
+                const i32x2_t w = {In<NAUT_BF16>::pack2(oacc[db][4 * g + 0] * inv_l, oacc[db][4 * g + 1] * inv_l),
+                                   In<NAUT_BF16>::pack2(oacc[db][4 * g + 2] * inv_l, oacc[db][4 * g + 3] * inv_l)};
+                *(i32x2_t*)(og + d * 2) = w;
+            }
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int S,
+                      int D, int causal, float scale, float descale_q, float descale_k, float descale_v, void* stream)
+{
+    if (!q || !k || !v || !o)
+        return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || S <= 0 || D <= 0)
+        return fail(NAUT_ERR_SHAPE, "B, Hq, Hkv, S and D must be positive");
+    if (Hq % Hkv != 0)
+        return fail(NAUT_ERR_SHAPE, "Hq must be a multiple of Hkv");
+    if (!std::isfinite(scale) || !std::isfinite(descale_q) || !std::isfinite(descale_k) || !std::isfinite(descale_v))
+        return fail(NAUT_ERR_SHAPE, "scale and the three descale factors must be finite");
+    if (scale < 0.f || descale_q <= 0.f || descale_k <= 0.f || descale_v <= 0.f)
+        return fail(NAUT_ERR_UNSUPPORTED, "scale must be >= 0 and the descale factors > 0");
+    if (D != 64 && D != 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    const long long nblocks = (long long)B * Hq * ((S + F8_BM - 1) / F8_BM);
+    if ((long long)B * Hq > 0x7fffffffLL || nblocks > 0x7fffffffLL)
+        return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15u)
+        return fail(NAUT_ERR_ALIGN, "q, k, v and o must be 16-byte aligned");
+    if ((uintptr_t)lse & 3u)
+        return fail(NAUT_ERR_ALIGN, "lse must be 4-byte aligned");
+
+    Fp8Params p;
+    p.q = q;
+    p.k = k;
+    p.v = v;
+    p.o = o;
+    p.lse = lse;
+    p.B = B;
+    p.Hq = Hq;
+    p.Hkv = Hkv;
+    p.S = S;
+    p.nqt = (S + F8_BM - 1) / F8_BM;
+    const float c = scale * descale_q * descale_k * 1.4426950408889634f;
+    p.c = c > 0.f ? c : 1e-30f;
+    p.dv = descale_v;
+    const dim3 grid((unsigned)nblocks);
+    hipStream_t st = (hipStream_t)stream;
+    if (D == 128) {
+        if (causal)
+            hipLaunchKernelGGL((naut_fwd_kernel_fp8<128, true>), grid, dim3(F8_THREADS), 0, st, p);
+        else
+            hipLaunchKernelGGL((naut_fwd_kernel_fp8<128, false>), grid, dim3(F8_THREADS), 0, st, p);
+    } else {
+        if (causal)
+            hipLaunchKernelGGL((naut_fwd_kernel_fp8<64, true>), grid, dim3(F8_THREADS), 0, st, p);
+        else
+            hipLaunchKernelGGL((naut_fwd_kernel_fp8<64, false>), grid, dim3(F8_THREADS), 0, st, p);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_launch(e);
+    return NAUT_OK;
+}
+
+}  // extern "C"

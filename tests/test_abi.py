@@ -141,3 +141,15 @@ def test_strided_argument_checks():
     assert call_s(good, q=None) == nb.NAUT_ERR_NULL
     # the dense entry points keep their contract: only 64 and 128
     assert call(D=96) == nb.NAUT_ERR_UNSUPPORTED
+
+
+def test_fp8_argument_checks():
+    def f8(q=A, k=A, v=A, o=A, lse=A, B=1, Hq=2, Hkv=2, S=128, D=128, causal=1, scale=0.1, dq=1.0, dk=1.0, dv=1.0):
+        return nb.naut_attn_fwd_fp8_raw(q, k, v, o, lse, B, Hq, Hkv, S, D, causal, scale, dq, dk, dv, None)
+    assert f8(v=None) == nb.NAUT_ERR_NULL
+    assert f8(S=0) == nb.NAUT_ERR_SHAPE
+    assert f8(Hkv=3) == nb.NAUT_ERR_SHAPE
+    assert f8(dk=float("nan")) == nb.NAUT_ERR_SHAPE
+    assert f8(dq=0.0) == nb.NAUT_ERR_UNSUPPORTED
+    assert f8(D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert f8(q=A + 4) == nb.NAUT_ERR_ALIGN
