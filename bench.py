@@ -35,7 +35,9 @@ MEASURED_TRAFFIC_BYTES = {
     "decode": 5.387e8,
 }
 
+PEAK_FP8_TFLOPS = 5033.2   # MI355X dense fp8 MFMA: twice the bf16 figure
 PEAK_HBM_GBS = 8000.0  # MI355X HBM3E
+FP8_DESCALE = {"q": 1.0 / 64, "k": 1.0 / 8, "v": 1.0 / 64}  # per-tensor scales of the synthetic FP8 inputs
 
 # Decode-time workload (the paper's second workload, Section 6): one new position per sequence against a
 # 16k-token key/value cache, 32 query heads on 8 K/V heads (a Qwen/GLM-like layout), B = 8.
@@ -110,6 +112,84 @@ def cpu_baseline(w, q, k, v, target_seconds: float):
                   % (n, total, dt),
         "seconds": dt,
     }
+
+
+def bench_fp8(args, nb, synth, torch, np) -> int:
+    """The long shape on FP8 (E4M3) inputs with per-tensor scales; one step = one naut_attn_fwd_fp8 call."""
+    w = synth.WORKLOADS["long"]
+    seed = synth.workload_seed(w)
+    dq, dk, dv = FP8_DESCALE["q"], FP8_DESCALE["k"], FP8_DESCALE["v"]
+    q = synth.fill_e4m3(w.B, w.Hq, w.S, w.D, seed, synth.TAG_Q, dq)
+    k = synth.fill_e4m3(w.B, w.Hkv, w.S, w.D, seed, synth.TAG_K, dk, w.n_outlier, w.outlier_scale)
+    v = synth.fill_e4m3(w.B, w.Hkv, w.S, w.D, seed, synth.TAG_V, dv)
+    qd, kd, vd = (torch.from_numpy(a).cuda() for a in (q, k, v))
+    o = torch.empty((w.B, w.Hq, w.S, w.D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        nb.naut_attn_fwd_fp8(qd, kd, vd, o, lse, w.causal, w.scale, dq, dk, dv, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    t0 = time.perf_counter()
+    ev.record(e0, stream.cuda_stream)
+    for _ in range(args.steps):
+        step()
+    ev.record(e1, stream.cuda_stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_wall = (t1 - t0) * 1e3 / args.steps
+    ms_kernel = ev.elapsed_ms(e0, e1) / args.steps
+    flops = w.flops
+    nq, nkv = w.B * w.Hq * w.S * w.D, w.B * w.Hkv * w.S * w.D
+    io_bytes = nq + 2 * nkv + nq * 2 + w.B * w.Hq * w.S * 4
+    out = {
+        "metric": "attention fwd TFLOP/s, FP8 E4M3 inputs (S=16k causal D=128)",
+        "value": flops / (ms_wall * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_wall,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp8_e4m3",
+        "data": "synthetic",
+        "config": {"workload": "long_fp8", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "D": w.D, "causal": w.causal,
+                   "outlier_k_rows": w.n_outlier, "descale": FP8_DESCALE, "kernel": "fwd_fp8_bm128_w4q32_bn64",
+                   "flop_convention": "4*B*Hq*S^2*D, halved for causal"},
+        "roofline": {"bound": "mfma", "achieved": flops / (ms_kernel * 1e-3) / 1e12, "peak": PEAK_FP8_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (ms_kernel * 1e-3) / 1e12 / PEAK_FP8_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get("long_fp8"), "kernel_ms": ms_kernel,
+                     "algorithmic_hbm_bytes": io_bytes},
+        "context": PAPER_CONTEXT,
+    }
+    if args.cpu_seconds > 0 and args.cpu_rows != 0:
+        import oracle
+        total = w.B * w.Hq * w.S
+        perm = np.random.default_rng(2604).permutation(total)
+
+        def run(rows):
+            rows = np.sort(rows).astype(np.int64)
+            t0 = time.perf_counter()
+            oracle.attn_rows_e4m3(q, k, v, dq, dk, dv, w.causal, w.scale, rows=rows)
+            dt = time.perf_counter() - t0
+            return dt, float((4.0 * w.D * ((rows % w.S) + 1)).sum())
+        dt0, _ = run(perm[:512])
+        dt_fixed, _ = run(perm[:1])
+        rate = max(dt0 - dt_fixed, 1e-3) / 512
+        n = int(min(total, max(512, (args.cpu_seconds - dt_fixed) / rate)))
+        dt, fl = run(perm[:n])
+        out["cpu_baseline"] = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(oracle.threads()), "kind": "oracle",
+                               "sample": "%d of %d query rows (uniform, seeded), %.1f s wall incl. fp64 decode of K,V"
+                               % (n, total, dt), "seconds": dt}
+    print(json.dumps(out))
+    return 0
 
 
 def bench_decode(args, nb, synth, torch, np) -> int:
@@ -188,8 +268,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long, or decode (a second, "
-                    "HBM-bound path: naut_attn_decode)")
+    ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long; decode (a second, HBM-bound "
+                    "path: naut_attn_decode); long_fp8 (the long shape on FP8 E4M3 inputs: naut_attn_fwd_fp8)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="seconds of CPU work the oracle baseline sample is sized for (0 = skip)")
     ap.add_argument("--cpu-rows", type=int, default=None, help="deprecated spelling: 0 skips the oracle baseline")
@@ -225,6 +305,8 @@ def main() -> int:
 
     if args.workload == "decode":
         return bench_decode(args, nb, synth, torch, np)
+    if args.workload == "long_fp8":
+        return bench_fp8(args, nb, synth, torch, np)
 
     w = synth.WORKLOADS[args.workload]
     q, k, v = synth.make_inputs(w)

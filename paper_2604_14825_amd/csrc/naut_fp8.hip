@@ -57,21 +57,26 @@ struct Fp8Params {
     float dv;       // descale_v
 };
 
-// K tile: 64 rows of D bytes; 16-byte chunks of a row XOR-ed with (row/2) so that the 32 lanes that read
-// the same chunk of 32 consecutive rows cover all banks.
+// K tile: 64 rows of D bytes, seen as 256-byte lines of 16-byte chunks; the chunk position inside a line
+// is XOR-ed with the line number (the layout of the 16-bit kernels, where it measures conflict-free): the
+// 32 lanes that read the same chunk of 32 consecutive rows then cover all banks.
 template <int D>
 __device__ __forceinline__ int k8_off(int row, int c16)
 {
     constexpr int CPR = D / 16;
-    return row * D + ((c16 ^ ((row >> 1) & (CPR - 1))) << 4);
+    const int L = row * CPR + c16;
+    const int line = L >> 4, pos = L & 15;
+    return (line << 8) + ((pos ^ (line & 15)) << 4);
 }
-// V tile: 32-byte chunks of a row XOR-ed with (row/2): the 16 rows x 32 bytes of one transposed read
-// then touch every bank twice, the minimum for 512 bytes.
+// V tile: rows of D bytes in 32-byte chunks.  One transposed read touches, per half of the wavefront, 8
+// rows (r0 + {0,1,2,3,8,9,10,11}) x 32 bytes = 256 bytes, one access per bank if the 8 rows land in 8
+// different bank groups: row parity gives two (128-byte rows) and the chunk position is XOR-ed with bits
+// 1 and 3 of the row number for the other four (D = 64: 64-byte rows, bits 0..1 give four, bit 3 the rest).
 template <int D>
 __device__ __forceinline__ int v8_off(int row, int c32)
 {
-    constexpr int CPR = D / 32;
-    return row * D + ((c32 ^ ((row >> 1) & (CPR - 1))) << 5);
+    const int key = D == 128 ? (((row >> 1) & 1) | (((row >> 3) & 1) << 1)) : ((row >> 3) & 1);
+    return row * D + ((c32 ^ key) << 5);
 }
 
 __device__ __forceinline__ int pack4_fp8(float x0, float x1, float x2, float x3)
