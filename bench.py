@@ -33,6 +33,8 @@ MEASURED_TRAFFIC_BYTES = {
     "long": 1.603e9,
     # profiles/naut_decode_B8_Hq32_Hkv8_Sk16384_D128.md: (262347 + 407) KiB x 2.000 read + (528 + 72) KiB written
     "decode": 5.387e8,
+    # profiles/naut_fwd_fp8_long_S16384_D128_causal.md: 564460 KiB x 2.000 read + 133123 KiB written
+    "long_fp8": 1.292e9,
 }
 
 PEAK_FP8_TFLOPS = 5033.2   # MI355X dense fp8 MFMA: twice the bf16 figure
