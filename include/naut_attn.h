@@ -62,7 +62,7 @@ typedef enum {
  * Fused attention forward, bf16 q/k/v -> bf16 o (round to nearest even), fp32 lse.
  * Arguments: device pointers as described above; B batch, Hq query heads, Hkv
  * key/value heads (Hq % Hkv == 0), S sequence length (queries and keys), D head
- * dimension (64 or 128); causal != 0 selects J_i = {0..i}; scale >= 0 multiplies
+ * dimension (64, 128 or 256); causal != 0 selects J_i = {0..i}; scale >= 0 multiplies
  * the scores (typically 1/sqrt(D)); stream as above.  Any S >= 1 is handled
  * (ragged tails are masked inside the kernel).
  * Returns NAUT_OK or a negative naut_status.
@@ -93,12 +93,12 @@ typedef struct {
 
 /*
  * The same operator on strided tensors and on other head dimensions (the paper's evaluation spans
- * models with "less common" head sizes, Section 7.1): D any multiple of 8 up to 128 -- a narrower
- * head runs on the 64- or 128-wide kernel with the missing columns of Q read as zero.  `st` gives
+ * models with less common head sizes, Section 7.1): D any multiple of 8 up to 256 -- a head runs on
+ * the next of the 64-, 128- and 256-wide kernels with the missing columns of Q read as zero.  `st` gives
  * element strides as above (NULL = contiguous [B][H][S][D]); q/k/v strides must be non-negative
  * multiples of 8 (16 bytes; 0 broadcasts a tensor along that axis), o strides positive multiples of 4,
  * every sequence stride at least D and at most 2^23.  lse stays contiguous [B][Hq][S].  Everything else
- * as naut_attn_fwd_dt, which is this call with st = NULL and D restricted to 64 or 128.
+ * as naut_attn_fwd_dt, which is this call with st = NULL and D restricted to 64, 128 or 256.
  */
 int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, float* lse,
                           int B, int Hq, int Hkv, int S, int D, int causal, float scale, void* stream,

@@ -66,12 +66,16 @@ struct Params {
     int cpr;       // real 16-byte chunks per row = head dimension / 8
 };
 
-// ---- kernel 1: 128 queries per work-group, 4 wavefronts x 32 queries, two work-groups per CU ----
+// ---- kernel 1: 128 queries per work-group, 4 wavefronts x 32 queries ----
+// Two work-groups per CU and 64 keys per step for D <= 128.  D = 256 doubles the O accumulator and the
+// Q fragments of a lane (192 registers between them), so it runs one work-group per CU on the full
+// 512-register budget, 32 keys per step (the four tile buffers then still fill 64 KB).
 
 template <int D, int DT_IN, int DT_OUT, bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS, 2) void naut_fwd_kernel_bm128(const Params p)
+__global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm128(const Params p)
 {
     using T = In<DT_IN>;
+    constexpr int BN = D > 128 ? 32 : 64;    // keys per step (hides the file-scope value used by kernel 2)
     constexpr int ROWB = D * 2;              // bytes per K/V row
     constexpr int TILEB = BN * ROWB;         // bytes per K or V tile
     constexpr int CPR = D / 8;               // 16-byte chunks per row
@@ -1015,7 +1019,8 @@ template <int D, int DT_IN, int DT_OUT>
 int launch(const Params& p, int causal, hipStream_t stream)
 {
     const long long nbh = (long long)p.B * p.Hq;
-    const int variant = pick_variant(p.S, nbh, D, causal);
+    // The pipelined kernel exists for D <= 128; wider heads always take the 128-query kernel.
+    const int variant = D > 128 ? V_BM128 : pick_variant(p.S, nbh, D, causal);
     const long long nblocks = nbh * (variant == V_BM128 ? p.nqt : p.nqt2);
     if (nblocks > 0x7fffffffLL)
         return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");
@@ -1027,15 +1032,21 @@ int launch(const Params& p, int causal, hipStream_t stream)
         else                                                                      \
             hipLaunchKernelGGL((KERNEL<D, DT_IN, DT_OUT, false NAUT_TAIL>), grid, dim3(THREADS), 0, stream, p); \
     } while (0)
-    if (variant == V_W8Q32) {
+    bool launched = false;
+    if constexpr (D <= 128) {
+        if (variant == V_W8Q32) {
 #define NAUT_TAIL , 1, 8
-        NAUT_LAUNCH(naut_fwd_kernel_v2, 512);
+            NAUT_LAUNCH(naut_fwd_kernel_v2, 512);
 #undef NAUT_TAIL
-    } else if (variant == V_W4Q64) {
+            launched = true;
+        } else if (variant == V_W4Q64) {
 #define NAUT_TAIL , 2, 4
-        NAUT_LAUNCH(naut_fwd_kernel_v2, 256);
+            NAUT_LAUNCH(naut_fwd_kernel_v2, 256);
 #undef NAUT_TAIL
-    } else {
+            launched = true;
+        }
+    }
+    if (!launched) {
 #define NAUT_TAIL
         NAUT_LAUNCH(naut_fwd_kernel_bm128, NTHREADS);
 #undef NAUT_TAIL
@@ -1072,8 +1083,8 @@ int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, 
         return fail(NAUT_ERR_SHAPE, "scale must be finite");
     if (scale < 0.f)
         return fail(NAUT_ERR_UNSUPPORTED, "negative scale is not supported");
-    if (D % 8 != 0 || D > 128)
-        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 8, at most 128");
+    if (D % 8 != 0 || D > 256)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 8, at most 256");
     if (!dtype_pair_ok(in_dtype, out_dtype))
         return fail(NAUT_ERR_UNSUPPORTED, "supported dtypes: q/k/v bf16 or f16; o of the same type or f32");
     if ((long long)B * Hq > 0x7fffffffLL || (long long)B * Hkv > 0x7fffffffLL)
@@ -1133,7 +1144,7 @@ int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, 
     p.o_rs = (int)(st->o_s * out_b);
     p.cpr = D / 8;
     hipStream_t st_ = (hipStream_t)stream;
-    const int DK = D <= 64 ? 64 : 128;  // width the kernel is compiled for
+    const int DK = D <= 64 ? 64 : D <= 128 ? 128 : 256;  // width the kernel is compiled for
 
 #define NAUT_DISPATCH(DD, IN, OUT)                         \
     if (DK == DD && in_dtype == IN && out_dtype == OUT)   \
@@ -1146,6 +1157,10 @@ int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, 
     NAUT_DISPATCH(64, NAUT_F16, NAUT_F16)
     NAUT_DISPATCH(128, NAUT_F16, NAUT_F32)
     NAUT_DISPATCH(64, NAUT_F16, NAUT_F32)
+    NAUT_DISPATCH(256, NAUT_BF16, NAUT_BF16)
+    NAUT_DISPATCH(256, NAUT_BF16, NAUT_F32)
+    NAUT_DISPATCH(256, NAUT_F16, NAUT_F16)
+    NAUT_DISPATCH(256, NAUT_F16, NAUT_F32)
 #undef NAUT_DISPATCH
     return fail(NAUT_ERR_UNSUPPORTED, "no kernel for this (D, dtype) combination");
 }
@@ -1153,8 +1168,8 @@ int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, 
 int naut_attn_fwd_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
                      int S, int D, int causal, float scale, void* stream, int in_dtype, int out_dtype)
 {
-    if (D > 0 && D != 64 && D != 128)
-        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128 (naut_attn_fwd_strided takes other head dimensions)");
+    if (D > 0 && D != 64 && D != 128 && D != 256)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64, 128 or 256 (naut_attn_fwd_strided takes other head dimensions)");
     return naut_attn_fwd_strided(q, k, v, o, lse, B, Hq, Hkv, S, D, causal, scale, stream, in_dtype, out_dtype, nullptr);
 }
 
@@ -1170,8 +1185,10 @@ int naut_version(void) { return 100; }
 
 const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int in_dtype, int out_dtype)
 {
-    if (B <= 0 || Hq <= 0 || S <= 0 || (D != 64 && D != 128) || !dtype_pair_ok(in_dtype, out_dtype))
+    if (B <= 0 || Hq <= 0 || S <= 0 || (D != 64 && D != 128 && D != 256) || !dtype_pair_ok(in_dtype, out_dtype))
         return nullptr;
+    if (D == 256)
+        return "fwd_bm128_w4q32_bn32";
     return kVariantName[pick_variant(S, (long long)B * Hq, D, causal)];
 }
 

@@ -68,7 +68,10 @@ __device__ __forceinline__ int k_off(int row, int c)
     constexpr int CPR = D / 8;  // chunks per row
     const int L = row * CPR + c;
     const int line = L >> 4, pos = L & 15;
-    return (line << 8) + ((pos ^ (line & 15)) << 4);
+    // A 512-byte row (D = 256) spans two lines: the key is the row number there, so that 16 consecutive
+    // rows still take 16 different positions.
+    const int key = CPR > 16 ? line >> 1 : line;
+    return (line << 8) + ((pos ^ (key & 15)) << 4);
 }
 
 // V is read transposed: one wavefront-wide read touches 8 consecutive rows x 64
@@ -77,8 +80,8 @@ __device__ __forceinline__ int k_off(int row, int c)
 template <int D>
 __device__ __forceinline__ int v_off(int row, int c)
 {
-    if constexpr (D == 128)
-        return row * 256 + ((c ^ ((row & 3) << 2)) << 4);
+    if constexpr (D >= 128)
+        return row * (D * 2) + ((c ^ ((row & 3) << 2)) << 4);
     else
         return row * 128 + ((c ^ (((row >> 1) & 1) << 2)) << 4);
 }

@@ -30,6 +30,7 @@ def test_version_and_variant_name():
     assert nb.variant_name(1, 32, 16384, 128, True, nb.NAUT_BF16, nb.NAUT_BF16) == "fwd_bm256_w8q32_bn64"
     assert nb.variant_name(1, 2, 256, 64, False, nb.NAUT_F16, nb.NAUT_F32) == "fwd_bm128_w4q32_bn64"
     assert nb.variant_name(8, 16, 1024, 96, False, nb.NAUT_BF16, nb.NAUT_BF16) is None
+    assert nb.variant_name(2, 8, 4096, 256, True, nb.NAUT_BF16, nb.NAUT_BF16) == "fwd_bm128_w4q32_bn32"
 
 
 def test_variant_rule_and_override(monkeypatch):
@@ -73,7 +74,8 @@ def call(q=A, k=A, v=A, o=A, lse=A, B=1, Hq=2, Hkv=2, S=128, D=64, causal=0, sca
     (dict(scale=float("inf")), nb.NAUT_ERR_SHAPE),
     (dict(scale=-1.0), nb.NAUT_ERR_UNSUPPORTED),
     (dict(D=96), nb.NAUT_ERR_UNSUPPORTED),
-    (dict(D=256), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(D=192), nb.NAUT_ERR_UNSUPPORTED),
+    (dict(D=512), nb.NAUT_ERR_UNSUPPORTED),
     (dict(dt=(nb.NAUT_F32, nb.NAUT_F32)), nb.NAUT_ERR_UNSUPPORTED),
     (dict(dt=(nb.NAUT_BF16, nb.NAUT_F16)), nb.NAUT_ERR_UNSUPPORTED),
     (dict(dt=(7, 0)), nb.NAUT_ERR_UNSUPPORTED),
@@ -133,13 +135,13 @@ def test_strided_argument_checks():
     bshd = lambda H, S, D: (S * H * D, D, H * D)
     good = bshd(2, 128, D) * 4
     assert call_s(good, D=100) == nb.NAUT_ERR_UNSUPPORTED     # not a multiple of 8
-    assert call_s(good, D=136) == nb.NAUT_ERR_UNSUPPORTED     # wider than the widest kernel
+    assert call_s(good, D=264) == nb.NAUT_ERR_UNSUPPORTED     # wider than the widest kernel
     assert call_s((good[0], good[1], good[2] + 4) + good[3:]) == nb.NAUT_ERR_ALIGN    # q rows not 16-byte aligned
     assert call_s(good[:9] + (good[9], good[10], 0)) == nb.NAUT_ERR_ALIGN             # o rows would coincide
     assert call_s(good[:5] + (D - 8,) + good[6:]) == nb.NAUT_ERR_SHAPE                # k rows overlap
     assert call_s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED        # v row stride too large
     assert call_s(good, q=None) == nb.NAUT_ERR_NULL
-    # the dense entry points keep their contract: only 64 and 128
+    # the dense entry points keep their contract: only 64, 128 and 256
     assert call(D=96) == nb.NAUT_ERR_UNSUPPORTED
 
 

@@ -113,3 +113,40 @@ def test_bshd_prefill_size_sampled_rows():
     rows = gu.sample_rows(w, 1500, 77)
     o_ref, lse_ref = oracle.attn_rows(q, k, v, w.in_dtype, w.causal, w.scale, rows=rows)
     gu.check(o.reshape(-1, w.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, "bshd prefill")
+
+
+@pytest.mark.parametrize("D,S,causal,idt,odt", [
+    (256, 333, True, synth.BF16, synth.F32),
+    (256, 500, False, synth.F16, synth.F16),
+    (136, 260, True, synth.BF16, synth.BF16),
+    (160, 129, False, synth.BF16, synth.F32),
+    (192, 1000, True, synth.F16, synth.F32),
+    (248, 97, True, synth.BF16, synth.BF16),
+    (256, 1, True, synth.BF16, synth.F32),
+])
+def test_wide_head_dimensions(D, S, causal, idt, odt):
+    """Head dimensions above 128 run on the 256-wide instantiation of the 128-query kernel (32 keys per step)."""
+    B, Hq, Hkv = 2, 4, 2
+    q, k, v = make(B, Hq, Hkv, S, D, idt, 9400 + D + S)
+    scale = 1.0 / math.sqrt(D)
+    print("wide head dim", D, S, flush=True)
+    qd, kd, vd = (gu.to_device(a, idt) for a in (q, k, v))
+    od = torch.full((B, Hq, S, D), float("nan"), dtype=gu.TORCH_DT[odt], device="cuda")
+    o, lse = run_strided(qd, kd, vd, od, causal, scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal, scale)
+    gu.check(o, lse, o_ref, lse_ref, "D=%d S=%d" % (D, S))
+
+
+def test_wide_head_bshd_long_sampled_rows():
+    """D = 256 at a prefill-sized sequence in sequence-major layout: many key steps, sampled rows."""
+    B, Hq, Hkv, S, D, idt = 1, 8, 2, 4096, 256, synth.BF16
+    q, k, v = make(B, Hq, Hkv, S, D, idt, 9500)
+    scale = 1.0 / math.sqrt(D)
+    bshd = lambda a: gu.to_device(np.ascontiguousarray(a.transpose(0, 2, 1, 3)), idt)
+    qd, kd, vd = bshd(q).transpose(1, 2), bshd(k).transpose(1, 2), bshd(v).transpose(1, 2)
+    o_mem = torch.full((B, S, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    o, lse = run_strided(qd, kd, vd, o_mem.transpose(1, 2), True, scale)
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([rng.integers(0, B * Hq * S, 600), [0, S - 1, B * Hq * S - 1]]))
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale, rows=rows)
+    gu.check(o.reshape(-1, D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, "bshd D=256")
