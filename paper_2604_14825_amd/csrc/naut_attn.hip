@@ -66,6 +66,43 @@ struct Params {
     int cpr;       // real 16-byte chunks per row = head dimension / 8
 };
 
+// S^T MFMAs of the variants that need more than 256 registers per lane (64 queries per wavefront in
+// kernel 2, D = 256 in kernel 1), written as asm so that their accumulator is an ordinary vector
+// register tuple while O and Q live in the accumulation registers (the compiler's own MFMA form
+// would then put the scores there too and copy each one out for the softmax).  The compiler's hazard handling does not look inside asm, so the wait states the
+// hardware does not interlock are owed by hand:
+//   - a vector instruction that writes an MFMA source (the register allocator may route a
+//     fragment through a copy) must be 2 wait states ahead of the MFMA: each asm starts with them;
+//   - an MFMA result may be read by a vector instruction only 11 wait states after the issue of
+//     this 8-pass MFMA: see `settle` and the guard at the start of kernel 2's `stage`.
+// Everything that fits the ordinary vector registers uses the compiler's MFMA throughout.
+template <int DT>
+struct XMfma;
+// Puts every later reader of an asm MFMA's result `d` the owed wait states behind that MFMA.
+__device__ __forceinline__ void settle(f32x16_t& d) { asm volatile("s_nop 11" : "+v"(d)); }
+template <>
+struct XMfma<NAUT_BF16> {
+    static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+    }
+    static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+    }
+};
+template <>
+struct XMfma<NAUT_F16> {
+    static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+    }
+    static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+    }
+};
+
 // ---- kernel 1: 128 queries per work-group, 4 wavefronts x 32 queries ----
 // Two work-groups per CU and 64 keys per step for D <= 128.  D = 256 doubles the O accumulator and the
 // Q fragments of a lane (192 registers between them), so it runs one work-group per CU on the full
@@ -84,11 +121,17 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     constexpr int DB = D / 32;               // 32-row blocks of O^T
     constexpr int KB = BN / 32;              // 32-key blocks of S^T
 
-    __shared__ __attribute__((aligned(256))) unsigned char smem[4 * TILEB];  // K0 V0 K1 V1
+    // D <= 128: K0 V0 K1 V1, filled through registers.  D = 256: four K buffers, then four V buffers,
+    // filled by direct global->LDS loads issued three steps ahead (one wavefront per SIMD has nothing
+    // else to hide the load latency behind, and no registers to stage tiles in).
+    constexpr bool WIDE = D > 128;
+    constexpr int NB = 4;                          // buffers per operand (wide)
+    constexpr int LDW = TILEB / 1024 / NWAVES;     // direct loads (1 KB each) per wavefront per tile (wide)
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[(WIDE ? 2 * NB : 4) * TILEB];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: it feeds scalar operands of the tile loads
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
@@ -119,14 +162,78 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         qf[ks] = ks * 2 + h < cpr ? *(const i32x4_t*)(qg + (size_t)my_q_ld * p.q_rs + ks * 32 + h * 16)
                                   : i32x4_t{0, 0, 0, 0};
     // Keep Q resident: without this the compiler re-issues the global loads inside the key loop.
+    // The wide instantiation keeps it, and O, in the accumulation registers.
+    auto pin_acc = [](f32x16_t& x) {
+        if constexpr (WIDE)
+            asm volatile("" : "+a"(x));
+    };
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        asm volatile("" : "+v"(qf[ks]));
+    for (int ks = 0; ks < KS; ++ks) {
+        if constexpr (WIDE)
+            asm volatile("" : "+a"(qf[ks]));
+        else
+            asm volatile("" : "+v"(qf[ks]));
+    }
 
     const int kv_end = CAUSAL ? (S < (qt + 1) * BM ? S : (qt + 1) * BM) : S;
     const int ntiles = (kv_end + BN - 1) / BN;
 
-    // global -> register staging of one K and one V tile
+    // wide: lane i of direct load n fills physical chunk P = (wave*LDW + n)*64 + i of the tile, so it
+    // fetches the logical (row, chunk) that k_off / v_off place there.
+    int wk_row[LDW], wk_col[LDW], wv_row[LDW], wv_col[LDW];
+    const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
+    if constexpr (WIDE) {
+#pragma unroll
+        for (int n = 0; n < LDW; ++n) {
+            const int P = (wave * LDW + n) * 64 + lane;
+            const int line = P >> 4, krow = line >> 1;
+            const int kc = ((line & 1) << 4) | ((P & 15) ^ (krow & 15));
+            wk_row[n] = krow;
+            wk_col[n] = (kc < cpr ? kc : cpr - 1) * 16;
+            const int vrow = P >> 5;
+            const int vc = (P & 31) ^ ((vrow & 3) << 2);
+            wv_row[n] = vrow;
+            wv_col[n] = (vc < cpr ? vc : cpr - 1) * 16;
+        }
+    }
+    // asm, so that the compiler does not make every later LDS read wait for these loads; completion
+    // is awaited explicitly (vmcnt) before the barrier that publishes the tile.
+    auto issue_tile = [&](int tile) {
+        const unsigned kd = smem_base + (unsigned)((tile % NB) * TILEB + wave * LDW * 1024);
+        const unsigned vd = kd + NB * TILEB;
+#pragma unroll
+        for (int n = 0; n < LDW; ++n) {
+            int row = tile * BN + wk_row[n];
+            row = row < S ? row : S - 1;
+            const int off = row * p.k_rs + wk_col[n];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(kd + n * 1024), "v"(off), "s"(kg)
+                         : "memory", "m0");
+        }
+#pragma unroll
+        for (int n = 0; n < LDW; ++n) {
+            int row = tile * BN + wv_row[n];
+            row = row < S ? row : S - 1;
+            const int off = row * p.v_rs + wv_col[n];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(vd + n * 1024), "v"(off), "s"(vg)
+                         : "memory", "m0");
+        }
+    };
+    // Waits until at most `ahead` later tiles of this wavefront's loads are still in flight.
+    auto wait_tiles = [&](int ahead) {
+        static_assert(2 * 2 * LDW < 64 || !WIDE, "vmcnt field");
+        if (ahead >= 2)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * 2 * LDW) : "memory");
+        else if (ahead == 1)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LDW) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+
+    // D <= 128: global -> register staging of one K and one V tile
     i32x4_t kst[LD_PER_T], vst[LD_PER_T];
     auto g_load = [&](int tile) {
 #pragma unroll
@@ -160,16 +267,30 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     float l_run = 0.f;        // this lane's share of the running sum (its 16 of every 32 keys)
     const float c = p.c;
 
-    g_load(0);
-    s_store(0);
-    __syncthreads();
+    if constexpr (WIDE) {
+        // Q must be in its registers before the tile loads start: the compiler's own wait for Q would
+        // otherwise also wait for every tile load issued before it.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        for (int t = 0; t < NB - 1 && t < ntiles; ++t)
+            issue_tile(t);
+        wait_tiles(ntiles - 1);
+        asm volatile("s_barrier" ::: "memory");
+    } else {
+        g_load(0);
+        s_store(0);
+        __syncthreads();
+    }
 
     for (int j = 0; j < ntiles; ++j) {
         const int buf = j & 1;
-        const unsigned char* kt = smem + buf * 2 * TILEB;
-        const unsigned char* vt = kt + TILEB;
+        const unsigned char* kt = WIDE ? smem + (j % NB) * TILEB : smem + buf * 2 * TILEB;
+        const unsigned char* vt = WIDE ? kt + NB * TILEB : kt + TILEB;
         const int kv0 = j * BN;
-        if (j + 1 < ntiles)
+        if constexpr (WIDE) {
+            // buffer (j + NB - 1) % NB was last read in step j - 1, which every wavefront has left
+            if (j + NB - 1 < ntiles)
+                issue_tile(j + NB - 1);
+        } else if (j + 1 < ntiles)
             g_load(j + 1);
 
         // Causal block skipping per wavefront: nothing to do if every key of the tile lies
@@ -179,13 +300,34 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             f32x16_t sacc[KB];
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
+                if constexpr (WIDE) {
+                    // The compiler moves nothing across the asm MFMAs, so the fragment reads are put
+                    // KPF MFMAs ahead of their use by hand (one read at a time would expose the whole
+                    // LDS latency 16 times per step).
+                    constexpr int KPF = 8;
+                    i32x4_t kf[KS];
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    sacc[kb][r] = 0.f;
+                    for (int ks = 0; ks < KPF; ++ks)
+                        kf[ks] = *(const i32x4_t*)(kt + k_off<D>(kb * 32 + l32, ks * 2 + h));
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const i32x4_t kf = *(const i32x4_t*)(kt + k_off<D>(kb * 32 + l32, ks * 2 + h));
-                    sacc[kb] = T::mfma(kf, qf[ks], sacc[kb]);
+                    for (int ks = 0; ks < KS; ++ks) {
+                        if (ks + KPF < KS)
+                            kf[ks + KPF] = *(const i32x4_t*)(kt + k_off<D>(kb * 32 + l32, (ks + KPF) * 2 + h));
+                        if (ks == 0)
+                            XMfma<DT_IN>::first(sacc[kb], kf[ks], qf[ks]);
+                        else
+                            XMfma<DT_IN>::acc(sacc[kb], kf[ks], qf[ks]);
+                    }
+                    settle(sacc[kb]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        sacc[kb][r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        const i32x4_t kf = *(const i32x4_t*)(kt + k_off<D>(kb * 32 + l32, ks * 2 + h));
+                        sacc[kb] = T::mfma(kf, qf[ks], sacc[kb]);
+                    }
                 }
             }
             // Mask only where the tile straddles the diagonal or the end of the sequence.
@@ -219,11 +361,17 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                 m_run = m_new;
                 l_run *= alpha;
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db) {
+                    pin_acc(oacc[db]);  // the copy into vector registers for the multiply starts here, not at the loop top
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         oacc[db][r] *= alpha;
+                    pin_acc(oacc[db]);
+                }
             }
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+                pin_acc(oacc[db]);
             const float m_new = m_run;
             float psum = 0.f;
 #pragma unroll
@@ -248,9 +396,17 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                 }
             }
         }
-        if (j + 1 < ntiles)
-            s_store(buf ^ 1);
-        __syncthreads();
+        if constexpr (WIDE) {
+            // Tile j + 1 must have landed; the tiles after it may fly on.  A bare barrier: every LDS
+            // read of this step has been consumed by its MFMA, and the fence of __syncthreads()
+            // would wait for all tile loads in flight.
+            wait_tiles(ntiles - 2 - j);
+            asm volatile("s_barrier" ::: "memory");
+        } else {
+            if (j + 1 < ntiles)
+                s_store(buf ^ 1);
+            __syncthreads();
+        }
     }
 
     // Epilogue: one division by l (the per-step divide/multiply pairs telescope away), lse, store.
@@ -341,42 +497,6 @@ __device__ __forceinline__ float half_sum(float x)
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
     return a + b;
 }
-
-// S^T MFMAs of the 64-queries-per-wavefront variant, written as asm so that their accumulator is
-// an ordinary vector register tuple while O and Q live in the accumulation registers (the
-// compiler's own MFMA form would then put the scores there too and copy each one out for the
-// softmax).  The compiler's hazard handling does not look inside asm, so the wait states the
-// hardware does not interlock are owed by hand:
-//   - a vector instruction that writes an MFMA source (the register allocator may route a
-//     fragment through a copy) must be 2 wait states ahead of the MFMA: each asm starts with them;
-//   - an MFMA result may be read by a vector instruction only 11 wait states after the issue of
-//     this 8-pass MFMA: see the guard at the start of `stage`.
-// The 32-queries-per-wavefront variant fits the ordinary vector registers entirely and uses the
-// compiler's MFMA throughout.
-template <int DT>
-struct XMfma;
-template <>
-struct XMfma<NAUT_BF16> {
-    static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
-    {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
-    }
-    static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
-    {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-    }
-};
-template <>
-struct XMfma<NAUT_F16> {
-    static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
-    {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
-    }
-    static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
-    {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-    }
-};
 
 // The softmax of a stage is cut into two pieces per score: FE (fma + exp2) and AC (row-sum add, and
 // for odd scores the pack to 16 bit).  FE of score e+1 is placed before AC of score e so that no
