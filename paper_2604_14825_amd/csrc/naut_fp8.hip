@@ -96,7 +96,7 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
