@@ -160,7 +160,19 @@ int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, fl
                         int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
                         void* workspace, size_t workspace_bytes, void* stream, int in_dtype, int out_dtype);
 
-/* Bytes of workspace naut_attn_decode[_dt] needs for these sizes; 0 if they are unsupported.  Host only. */
+/*
+ * The same on strided tensors: `st` gives element strides of the batch, head and sequence axes (the D axis
+ * is contiguous) of q and o, indexed [B][Hq][Sq][D], and of k and v, indexed [B][Hkv][Sk][D] -- e.g. a
+ * sequence-major K/V cache [B][Sk][Hkv][D] has {Sk*Hkv*D, D, Hkv*D}.  Same rules as naut_attn_fwd_strided
+ * (q/k/v strides non-negative multiples of 8, o strides positive multiples of 4, sequence strides between D
+ * and 2^23); st = NULL means contiguous, which is what naut_attn_decode_dt passes.  lse stays dense.
+ */
+int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* o, float* lse,
+                             int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
+                             void* workspace, size_t workspace_bytes, void* stream, int in_dtype, int out_dtype,
+                             const naut_strides* st);
+
+/* Bytes of workspace naut_attn_decode[_dt|_strided] needs for these sizes; 0 if they are unsupported.  Host only. */
 size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D);
 
 #ifdef __cplusplus

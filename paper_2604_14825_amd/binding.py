@@ -25,7 +25,7 @@ NAUT_F32 = 2
 
 EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
            "naut_attn_variant_name", "naut_attn_decode", "naut_attn_decode_dt", "naut_attn_decode_workspace_bytes",
-           "naut_attn_fwd_strided", "naut_attn_fwd_fp8")
+           "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided")
 
 
 class NautStrides(ctypes.Structure):
@@ -74,6 +74,9 @@ def lib():
         L.naut_attn_decode_dt.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci]
         L.naut_attn_decode_workspace_bytes.restype = sz
         L.naut_attn_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+        L.naut_attn_decode_strided.restype = ci
+        L.naut_attn_decode_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci,
+                                               ctypes.POINTER(NautStrides)]
         _lib = L
     return _lib
 
@@ -192,6 +195,49 @@ def naut_attn_decode(q, k, v, o, lse, causal: bool, scale: float, workspace, str
         raise NautError(rc, last_error_string())
 
 
+def naut_attn_decode_strided_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale, ws_ptr,
+                                 ws_bytes, stream_ptr, in_dtype, out_dtype, strides) -> int:
+    """Direct call with integer device addresses; `strides` is a NautStrides, a 12-tuple or None."""
+    if strides is not None and not isinstance(strides, NautStrides):
+        strides = NautStrides(*[int(x) for x in strides])
+    ref = ctypes.byref(strides) if strides is not None else None
+    return int(lib().naut_attn_decode_strided(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, int(causal),
+                                              float(scale), ws_ptr, ws_bytes, stream_ptr, int(in_dtype),
+                                              int(out_dtype), ref))
+
+
+def naut_attn_decode_strided(q, k, v, o, lse, causal: bool, scale: float, workspace, stream=None):
+    """Decode-time attention on torch device tensors indexed q,o [B,Hq,Sq,D] and k,v [B,Hkv,Sk,D] with arbitrary
+    batch/head/sequence strides (e.g. `cache.transpose(1, 2)` of a [B,Sk,Hkv,D] cache); the D axis contiguous.
+    lse: contiguous fp32 [B,Hq,Sq] or None; workspace: contiguous, at least decode_workspace_bytes(...) bytes."""
+    import torch
+    for t in (q, k, v, o):
+        if not (t.is_cuda and t.dim() == 4 and t.stride(3) == 1):
+            raise ValueError("q, k, v, o must be 4-d device tensors with a contiguous last axis")
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous device tensor")
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    if tuple(k.shape) != (B, Hkv, Sk, D) or tuple(v.shape) != (B, Hkv, Sk, D) or tuple(o.shape) != (B, Hq, Sq, D):
+        raise ValueError("shape mismatch between q, k, v, o")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share one dtype")
+    lse_ptr = None
+    if lse is not None:
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, Hq, Sq)):
+            raise ValueError("lse must be a contiguous fp32 device tensor [B,Hq,Sq]")
+        lse_ptr = lse.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    st = NautStrides(*[t.stride(a) for t in (q, k, v, o) for a in (0, 1, 2)])
+    rc = naut_attn_decode_strided_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, Sq,
+                                      Sk, D, causal, scale, workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), stream.cuda_stream,
+                                      _torch_dtype_code(q), _torch_dtype_code(o), st)
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())
+
+
 def naut_attn_fwd_strided_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, S, D, causal, scale, stream_ptr,
                               in_dtype, out_dtype, strides) -> int:
     """Direct call with integer device addresses; `strides` is a NautStrides, a 12-tuple or None."""
@@ -204,7 +250,7 @@ def naut_attn_fwd_strided_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, S
 
 def naut_attn_fwd_strided(q, k, v, o, lse, causal: bool, scale: float, stream=None):
     """Attention forward on torch device tensors indexed [B,H,S,D] with arbitrary batch/head/sequence strides
-    (e.g. `x.transpose(1, 2)` of a [B,S,H,D] tensor); the D axis must be contiguous, D any multiple of 8 <= 128.
+    (e.g. `x.transpose(1, 2)` of a [B,S,H,D] tensor); the D axis must be contiguous, D any multiple of 8 <= 256.
     lse: contiguous fp32 [B,Hq,S] or None."""
     import torch
     for t in (q, k, v, o):

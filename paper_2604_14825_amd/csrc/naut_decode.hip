@@ -56,6 +56,9 @@ struct DecodeParams {
     int bps;       // 32-key blocks per split (a multiple of 4)
     int causal;
     float c;       // scale * log2(e), > 0
+    // byte strides of batch, head and sequence position (the D axis is contiguous)
+    long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
+    int q_rs, k_rs, v_rs, o_rs;
 };
 
 __device__ __forceinline__ float half_sum_f(float x)
@@ -91,10 +94,10 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     const int Sk = p.Sk;
     const float c = p.c;
 
-    // The R rows of this (batch, K/V head) are contiguous: [R][D] starting at query head hk*g.
-    const unsigned char* qg = (const unsigned char*)p.q + (size_t)(b * p.Hq + hk * g) * p.Sq * ROWB;
-    const unsigned char* kg = (const unsigned char*)p.k + (size_t)bhk * Sk * ROWB;
-    const unsigned char* vg = (const unsigned char*)p.v + (size_t)bhk * Sk * ROWB;
+    // The R rows of this (batch, K/V head): row r is position r % Sq of query head hk*g + r / Sq.
+    const unsigned char* qg = (const unsigned char*)p.q + b * p.q_bs + (long long)(hk * g) * p.q_hs;
+    const unsigned char* kg = (const unsigned char*)p.k + b * p.k_bs + hk * p.k_hs;
+    const unsigned char* vg = (const unsigned char*)p.v + b * p.v_bs + hk * p.v_hs;
 
     const int row = chunk * DEC_ROWS + l32;                 // the query row this lane owns
     const int row_ld = row < p.R ? row : p.R - 1;
@@ -104,27 +107,32 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     i32x4_t qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = *(const i32x4_t*)(qg + (size_t)row_ld * ROWB + ks * 32 + h * 16);
+        qf[ks] = *(const i32x4_t*)(qg + (row_ld / p.Sq) * p.q_hs + (long long)(row_ld % p.Sq) * p.q_rs + ks * 32 + h * 16);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
         asm volatile("" : "+v"(qf[ks]));
 
     // Direct global->LDS loads: instruction n fills physical chunks 64n..64n+63 of the block, lane i
     // the chunk 64n+i, so the lane fetches the logical chunk that the swizzle maps there.
-    int k_go[NLD], v_go[NLD];
+    // (row of the block, byte inside the row) of that logical chunk:
+    int k_row[NLD], k_col[NLD], v_row[NLD], v_col[NLD];
 #pragma unroll
     for (int n = 0; n < NLD; ++n) {
         const int P = n * 64 + lane;
         {
             const int line = P >> 4, pos = P & 15;
-            k_go[n] = ((line << 4) + (pos ^ (line & 15))) * 16;
+            const int off = ((line << 4) + (pos ^ (line & 15))) * 16;  // byte offset in a dense [32][D] block
+            k_row[n] = off / ROWB;
+            k_col[n] = off % ROWB;
         }
         if constexpr (D == 128) {
             const int r = P >> 4, cc = P & 15;
-            v_go[n] = r * ROWB + (cc ^ ((r & 3) << 2)) * 16;
+            v_row[n] = r;
+            v_col[n] = (cc ^ ((r & 3) << 2)) * 16;
         } else {
             const int r = P >> 3, cc = P & 7;
-            v_go[n] = r * ROWB + (cc ^ (((r >> 1) & 1) << 2)) * 16;
+            v_row[n] = r;
+            v_col[n] = (cc ^ (((r >> 1) & 1) << 2)) * 16;
         }
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem + (unsigned)(wave * 4 * BLKB);
@@ -135,17 +143,18 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     const int blk_end = blk_begin + p.bps < nblk ? blk_begin + p.bps : nblk;
 
     auto issue = [&](int blk, int buf) {
-        const unsigned char* kp = kg + (size_t)blk * BLKB;
-        const unsigned char* vp = vg + (size_t)blk * BLKB;
+        const unsigned char* kp = kg + (size_t)blk * DEC_BLK * p.k_rs;
+        const unsigned char* vp = vg + (size_t)blk * DEC_BLK * p.v_rs;
         const int rows_left = Sk - blk * DEC_BLK;  // >= 1
         const unsigned dst = lds0 + (unsigned)(buf * 2 * BLKB);
 #pragma unroll
         for (int n = 0; n < NLD; ++n) {
-            int ko = k_go[n], vo = v_go[n];
+            int kr = k_row[n], vr = v_row[n];
             if (rows_left < DEC_BLK) {  // ragged last block: re-read the last row instead of running past the end
-                ko = ko / ROWB < rows_left ? ko : (rows_left - 1) * ROWB + ko % ROWB;
-                vo = vo / ROWB < rows_left ? vo : (rows_left - 1) * ROWB + vo % ROWB;
+                kr = kr < rows_left ? kr : rows_left - 1;
+                vr = vr < rows_left ? vr : rows_left - 1;
             }
+            const int ko = kr * p.k_rs + k_col[n], vo = vr * p.v_rs + v_col[n];
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
                          : "s"(dst + n * 1024), "v"(ko), "s"(kp)
@@ -359,20 +368,22 @@ __global__ __launch_bounds__(MRG_THREADS) void naut_decode_merge_kernel(const De
     for (int e = 0; e < EPT; ++e)
         acc[e] = red_o[0][lane * EPT + e] + red_o[1][lane * EPT + e] + red_o[2][lane * EPT + e] + red_o[3][lane * EPT + e];
     const float inv_l = 1.0f / L;
-    // global row index: the R rows of (batch, K/V head) bhk are contiguous in o and lse
-    const size_t grow = (size_t)bhk * p.R + r;
+    // lse is dense [B][Hq][Sq]: the R rows of (batch, K/V head) bhk are contiguous there
     if (p.lse != nullptr && lane == 0)
-        p.lse[grow] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
+        p.lse[(size_t)bhk * p.R + r] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
+    const int b = bhk / p.Hkv, hk = bhk % p.Hkv;
+    const int head = hk * (p.Hq / p.Hkv) + r / p.Sq, pos = r % p.Sq;
+    unsigned char* orow = (unsigned char*)p.o + b * p.o_bs + head * p.o_hs + (long long)pos * p.o_rs;
     if constexpr (DT_OUT == NAUT_F32) {
-        float* og = (float*)p.o + grow * D + lane * EPT;
+        float* og = (float*)orow + lane * EPT;
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             og[e] = acc[e] * inv_l;
     } else if constexpr (EPT == 2) {
-        int* og = (int*)((unsigned char*)p.o + (grow * D + lane * EPT) * 2);
+        int* og = (int*)(orow + lane * EPT * 2);
         *og = In<DT_OUT>::pack2(acc[0] * inv_l, acc[1] * inv_l);
     } else {
-        unsigned short* og = (unsigned short*)p.o + grow * D + lane;
+        unsigned short* og = (unsigned short*)orow + lane;
         *og = (unsigned short)(In<DT_OUT>::pack2(acc[0] * inv_l, 0.f) & 0xffff);
     }
 }
@@ -433,9 +444,9 @@ size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, 
     return pl.ws_bytes;
 }
 
-int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
-                        int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
-                        void* stream, int in_dtype, int out_dtype)
+int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                             int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
+                             void* stream, int in_dtype, int out_dtype, const naut_strides* st)
 {
     if (!q || !k || !v || !o)
         return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
@@ -463,6 +474,27 @@ int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, fl
     if (!workspace || workspace_bytes < pl.ws_bytes)
         return fail(NAUT_ERR_SHAPE, "workspace is NULL or smaller than naut_attn_decode_workspace_bytes()");
 
+    naut_strides cs;  // contiguous q, o [B][Hq][Sq][D] and k, v [B][Hkv][Sk][D]
+    cs.q_s = cs.k_s = cs.v_s = cs.o_s = D;
+    cs.q_h = cs.o_h = (long long)Sq * D;
+    cs.k_h = cs.v_h = (long long)Sk * D;
+    cs.q_b = cs.o_b = (long long)Hq * Sq * D;
+    cs.k_b = cs.v_b = (long long)Hkv * Sk * D;
+    if (!st)
+        st = &cs;
+    const long long in_strides[9] = {st->q_b, st->q_h, st->q_s, st->k_b, st->k_h, st->k_s, st->v_b, st->v_h, st->v_s};
+    for (long long x : in_strides)
+        if (x < 0 || x % 8 != 0)
+            return fail(NAUT_ERR_ALIGN, "q/k/v strides must be non-negative multiples of 8 elements (16 bytes)");
+    if (st->o_b <= 0 || st->o_h <= 0 || st->o_s <= 0 || st->o_b % 4 != 0 || st->o_h % 4 != 0 || st->o_s % 4 != 0)
+        return fail(NAUT_ERR_ALIGN, "o strides must be positive multiples of 4 elements");
+    if (st->q_s < D || st->k_s < D || st->v_s < D || st->o_s < D)
+        return fail(NAUT_ERR_SHAPE, "a sequence stride is smaller than D: rows would overlap");
+    const long long max_rs = 1LL << 23;  // elements: keeps 32 rows of byte offsets inside 32 bits
+    if (st->q_s > max_rs || st->k_s > max_rs || st->v_s > max_rs || st->o_s > max_rs)
+        return fail(NAUT_ERR_UNSUPPORTED, "sequence stride too large");
+    const int out_b = out_dtype == NAUT_F32 ? 4 : 2;
+
     DecodeParams p;
     p.q = q;
     p.k = k;
@@ -482,10 +514,22 @@ int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, fl
     p.causal = causal ? 1 : 0;
     const float cc = scale * 1.4426950408889634f;
     p.c = cc > 0.f ? cc : 1.0e-30f;  // scale == 0: every score becomes (almost exactly) 0, the softmax uniform
-    hipStream_t st = (hipStream_t)stream;
+    p.q_bs = st->q_b * 2;
+    p.q_hs = st->q_h * 2;
+    p.q_rs = (int)(st->q_s * 2);
+    p.k_bs = st->k_b * 2;
+    p.k_hs = st->k_h * 2;
+    p.k_rs = (int)(st->k_s * 2);
+    p.v_bs = st->v_b * 2;
+    p.v_hs = st->v_h * 2;
+    p.v_rs = (int)(st->v_s * 2);
+    p.o_bs = st->o_b * out_b;
+    p.o_hs = st->o_h * out_b;
+    p.o_rs = (int)(st->o_s * out_b);
+    hipStream_t hs = (hipStream_t)stream;
 #define NAUT_DEC(DD, IN, OUT)                                  \
     if (D == DD && in_dtype == IN && out_dtype == OUT)         \
-        return launch_decode<DD, IN, OUT>(p, st);
+        return launch_decode<DD, IN, OUT>(p, hs);
     NAUT_DEC(128, NAUT_BF16, NAUT_BF16)
     NAUT_DEC(128, NAUT_BF16, NAUT_F32)
     NAUT_DEC(128, NAUT_F16, NAUT_F16)
@@ -496,6 +540,14 @@ int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, fl
     NAUT_DEC(64, NAUT_F16, NAUT_F32)
 #undef NAUT_DEC
     return fail(NAUT_ERR_UNSUPPORTED, "no kernel for this (D, dtype) combination");
+}
+
+int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                        int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
+                        void* stream, int in_dtype, int out_dtype)
+{
+    return naut_attn_decode_strided(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale, workspace, workspace_bytes,
+                                    stream, in_dtype, out_dtype, nullptr);
 }
 
 int naut_attn_decode(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int Sq,

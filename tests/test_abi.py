@@ -121,6 +121,23 @@ def test_decode_argument_checks():
     assert dec(wsb=ws - 1) == nb.NAUT_ERR_SHAPE
     assert "workspace" in nb.last_error_string()
 
+    # strided variant: same stride rules as the strided prefill entry point
+    bf = nb.NAUT_BF16
+    B, Hq, Hkv, Sq, Sk, D = 1, 8, 2, 1, 4096, 128
+    good = (Hq * Sq * D, Sq * D, D, Sk * Hkv * D, D, Hkv * D, Sk * Hkv * D, D, Hkv * D, Hq * Sq * D, Sq * D, D)
+
+    def dec_s(strides, q=A, **kw):
+        a = dict(ok)
+        a.update(kw)
+        return nb.naut_attn_decode_strided_raw(q, A, A, A, A, a["B"], a["Hq"], a["Hkv"], a["Sq"], a["Sk"], a["D"],
+                                               a["causal"], a["scale"], A, ws, None, bf, bf, strides)
+    assert dec_s(good, q=None) == nb.NAUT_ERR_NULL
+    assert dec_s(good[:5] + (Hkv * D + 4,) + good[6:]) == nb.NAUT_ERR_ALIGN          # k rows not 16-byte aligned
+    assert dec_s(good[:5] + (D - 8,) + good[6:]) == nb.NAUT_ERR_SHAPE                # k rows overlap
+    assert dec_s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED        # v row stride too large
+    assert dec_s(good[:9] + (0,) + good[10:]) == nb.NAUT_ERR_ALIGN                   # o batch stride must be positive
+    assert dec_s(good, D=96) == nb.NAUT_ERR_UNSUPPORTED
+
 
 def test_strided_argument_checks():
     bf = nb.NAUT_BF16

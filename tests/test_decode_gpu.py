@@ -101,3 +101,57 @@ def test_decode_rejects_short_workspace():
     with pytest.raises(nb.NautError) as e:
         nb.naut_attn_decode(q, k, k, o, None, True, 0.1, ws)
     assert e.value.code == nb.NAUT_ERR_SHAPE
+
+
+def _bshd(a, dt):
+    """Device copy stored [B][S][H][D], returned as the logical [B,H,S,D] view."""
+    return gu.to_device(np.ascontiguousarray(a.transpose(0, 2, 1, 3)), dt).transpose(1, 2)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal,idt,odt", [
+    (2, 8, 2, 1, 777, 128, True, synth.BF16, synth.BF16),
+    (1, 16, 2, 5, 300, 128, True, synth.BF16, synth.F32),
+    (3, 6, 3, 2, 2049, 64, True, synth.F16, synth.F16),
+    (2, 4, 4, 7, 1000, 64, False, synth.BF16, synth.BF16),
+])
+def test_decode_sequence_major_cache(B, Hq, Hkv, Sq, Sk, D, causal, idt, odt):
+    """K/V cache and queries stored [B][S][H][D]; O written in the same layout; the gaps of a padded O untouched."""
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, idt, 7500 + Sk + D + Sq, Sk // 50)
+    scale = 1.0 / math.sqrt(D)
+    qd, kd, vd = _bshd(q, idt), _bshd(k, idt), _bshd(v, idt)
+    assert not kd.is_contiguous()
+    P = D + 16                                                            # O rows padded to a wider pitch
+    o_mem = torch.full((B, Sq, Hq, P), 7.0, dtype=gu.TORCH_DT[odt], device="cuda")
+    od = o_mem[..., :D].transpose(1, 2)
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    print("decode bshd", B, Hq, Hkv, Sq, Sk, D, flush=True)
+    nb.naut_attn_decode_strided(qd, kd, vd, od, lse, causal, scale, ws)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, causal, scale)
+    gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode bshd")
+    assert torch.all(o_mem[..., D:] == 7.0).item(), "the gaps between O rows were written"
+
+
+def test_decode_shared_cache_and_padded_rows():
+    """One K/V cache shared by every batch entry (batch stride 0), rows padded to a wider pitch with NaN gaps."""
+    B, Hq, Hkv, Sq, Sk, D, idt = 3, 8, 2, 1, 1200, 128, synth.BF16
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, idt, 7600, Sk // 50)
+    k[1:], v[1:] = k[0], v[0]
+    scale = 1.0 / math.sqrt(D)
+
+    def padded_shared(a):
+        buf = np.full((1, Hkv, Sk, D + 64), 0x7FC0, dtype=np.uint16)     # bf16 NaN in the gaps
+        buf[..., :D] = a[:1]
+        return gu.to_device(buf, idt)[..., :D].expand(B, Hkv, Sk, D)
+    kd, vd = padded_shared(k), padded_shared(v)
+    assert kd.stride(0) == 0 and kd.stride(2) == D + 64
+    qd = gu.to_device(q, idt)
+    od = torch.full((B, Hq, Sq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D), dtype=torch.uint8, device="cuda")
+    nb.naut_attn_decode_strided(qd, kd, vd, od, lse, True, scale, ws)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, True, scale)
+    gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode shared cache")
