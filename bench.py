@@ -35,6 +35,8 @@ MEASURED_TRAFFIC_BYTES = {
     "decode": 5.387e8,
     # profiles/naut_fwd_fp8_long_S16384_D128_causal.md: 564460 KiB x 2.000 read + 133123 KiB written
     "long_fp8": 1.292e9,
+    # profiles/naut_fwd_bm128_w4q32_bn32_long_S16384_D256_causal.md: 2604500 KiB x 2.000 read + 264190 KiB written
+    "long_d256": 5.60e9,
 }
 
 PEAK_FP8_TFLOPS = 5033.2   # MI355X dense fp8 MFMA: twice the bf16 figure
@@ -270,8 +272,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long; decode (a second, HBM-bound "
-                    "path: naut_attn_decode); long_fp8 (the long shape on FP8 E4M3 inputs: naut_attn_fwd_fp8)")
+    ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long; long_d256 (the long shape at "
+                    "D = 256); decode (a second, HBM-bound path: naut_attn_decode); long_fp8 (the long shape on "
+                    "FP8 E4M3 inputs: naut_attn_fwd_fp8)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="seconds of CPU work the oracle baseline sample is sized for (0 = skip)")
     ap.add_argument("--cpu-rows", type=int, default=None, help="deprecated spelling: 0 skips the oracle baseline")

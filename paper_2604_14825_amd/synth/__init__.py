@@ -72,6 +72,8 @@ WORKLOADS = {
     "prefill": Workload("prefill", 4, 32, 32, 4096, 128, True, BF16, BF16),
     "gqa": Workload("gqa", 2, 64, 8, 8192, 128, True, BF16, BF16),
     "long": Workload("long", 1, 32, 32, 16384, 128, True, BF16, BF16, 0.01, 8.0),
+    # not one of the five benchmark configurations: the long shape at the widest head dimension
+    "long_d256": Workload("long_d256", 1, 32, 32, 16384, 256, True, BF16, BF16, 0.01, 8.0),
 }
 WORKLOAD_ORDER = ["tiny", "encoder", "prefill", "gqa", "long"]
 
