@@ -675,14 +675,23 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     struct TileLoad {
         unsigned dst;             // LDS byte address of this wavefront's part of the tile
         const unsigned char* gt;  // global address of the tile (wave-uniform)
-        bool last;                // the tile is the last one: use the second set of offsets
     };
-    auto tile_load = [&](const unsigned char* g, int row_stride, unsigned lds_tiles, int tile) {
+    // `buf` is the LDS buffer the tile goes to (tile % NBUF, a constant at every call site).  Once the
+    // last tile is reached the per-lane offsets are replaced, for good, by the ragged-tail set: a
+    // wave-uniform branch taken a few times per work-group instead of a select per load.
+    auto tile_load = [&](const unsigned char* g, int row_stride, unsigned lds_tiles, int tile, int buf,
+                         int (&goff)[LD_PER_W], const int (&goff_last)[LD_PER_W]) {
         TileLoad t;
         const int tl = tile < ntiles ? tile : ntiles - 1;
-        t.dst = lds_tiles + (unsigned)((tile % NBUF) * TILEB + wave * LD_PER_W * 1024);
+        t.dst = lds_tiles + (unsigned)(buf * TILEB + wave * LD_PER_W * 1024);
         t.gt = g + ((ABL & 128) ? (size_t)0 : (size_t)tl * BN * row_stride);
-        t.last = tile >= ntiles - 1;
+        if (tile >= ntiles - 1) {
+#pragma unroll
+            for (int i = 0; i < LD_PER_W; ++i) {
+                goff[i] = goff_last[i];
+                asm volatile("" : "+v"(goff[i]));  // keeps this a branch: nothing here can be speculated into a select
+            }
+        }
         return t;
     };
     // asm, so that the compiler does not make every later LDS read wait for these loads;
@@ -695,8 +704,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             asm volatile("" : "+v"(sink[i]));
         }
     }
-    auto issue_load = [&](const TileLoad& t, int i, const int* goff, const int* goff_last) {
-        const int off = (ABL & 128) ? 0 : (t.last ? goff_last[i] : goff[i]);
+    auto issue_load = [&](const TileLoad& t, int i, const int* goff) {
+        const int off = (ABL & 128) ? 0 : goff[i];
         if constexpr ((ABL & 64) != 0) {
             asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(sink[i & 3]) : "v"(off), "s"(t.gt) : "memory");
             return;
@@ -721,6 +730,19 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             const int d = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
             v_lane[db] = v_off<D>(key, d >> 3) + (d & 7) * 2;
         }
+    }
+    // LDS byte addresses of the fragments in buffer 0 of K and of V; they stay as they are for the whole
+    // kernel (buffer, block and step offsets are immediates)
+    int k_it[KS], v_it[DB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        k_it[ks] = k_lane[ks] + (int)k_lds;
+        asm volatile("" : "+v"(k_it[ks]));  // opaque: the compiler then adds nothing but instruction immediates to it
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        v_it[db] = v_lane[db] + (int)v_lds;
+        asm volatile("" : "+v"(v_it[db]));
     }
 
     f32x16_t oacc[QH][DB];
@@ -761,41 +783,44 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 
     // Fragment f of block BLKX: even f = V^T (two transposed 64-bit reads), odd f = K (one 128-bit
     // read).  NEXT selects the tiles of the next iteration (same lane addresses plus a scalar delta).
-    auto load_frag = [&](auto F, auto BLKX, auto NEXT, const int (&k_it)[KS], const int (&v_it)[DB], int kdelta,
-                         int vdelta) -> i32x4_t {
-        constexpr int f = decltype(F)::value, BLK = decltype(BLKX)::value;
+    // U = iteration index mod NBUF: iteration j reads K tile j from buffer U and V tile j-1 from buffer
+    // U-1 (mod NBUF), so with the key loop unrolled NBUF times every buffer offset is an immediate of
+    // the LDS instruction and the per-lane addresses never change.
+    auto load_frag = [&](auto F, auto BLKX, auto NEXT, auto UC) -> i32x4_t {
+        constexpr int f = decltype(F)::value, BLK = decltype(BLKX)::value, U = decltype(UC)::value;
         constexpr bool next_iter = decltype(NEXT)::value;
+        constexpr int KOFF = (next_iter ? (U + 1) % NBUF : U) * TILEB;
+        constexpr int VOFF = (next_iter ? U : (U + NBUF - 1) % NBUF) * TILEB;
         if constexpr ((ABL & 2) != 0) {
             i32x4_t fr;
             asm volatile("" : "=v"(fr));
             return fr;
         } else if constexpr (f % 2 == 0 && (ABL & 32) != 0) {  // timing only: V^T fragment as one plain 128-bit read
             constexpr int y = f / 2, t = y / DB, db = y % DB;
-            const int a = next_iter ? k_it[db + 4 * t] + kdelta : k_it[db + 4 * t];
+            const int a = k_it[db + 4 * t] + KOFF;
             return *(const NAUT_LDS i32x4_t*)(uintptr_t)(a + BLK * 32 * ROWB + NBUF * TILEB);
         } else if constexpr (f % 2 == 0) {
             constexpr int y = f / 2, t = y / DB, db = y % DB;
             constexpr int off = (BLK * 32 + 16 * t) * ROWB;
-            const int a = next_iter ? v_it[db] + vdelta : v_it[db];
+            const int a = v_it[db] + VOFF;
             const i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(a + off));
             const i16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(a + off + 8 * ROWB));
             const i32x2_t lo = __builtin_bit_cast(i32x2_t, r0), hi = __builtin_bit_cast(i32x2_t, r1);
             return i32x4_t{lo.x, lo.y, hi.x, hi.y};
         } else {
             constexpr int ks = f / 2;
-            const int a = next_iter ? k_it[ks] + kdelta : k_it[ks];
+            const int a = k_it[ks] + KOFF;
             return *(const NAUT_LDS i32x4_t*)(uintptr_t)(a + BLK * 32 * ROWB);
         }
     };
 
-    // One pipeline stage k = 2*j - 1 + BLK of iteration j: Y(k-1) reads block BLK of the V tile in
-    // v_it, X(k+1) block BLK of the K tile in k_it.  Every wavefront runs every stage: blocks that
+    // One pipeline stage k = 2*j - 1 + BLK of iteration j (j mod NBUF = U): Y(k-1) reads block BLK of V
+    // tile j-1, X(k+1) block BLK of K tile j.  Every wavefront runs every stage: blocks that
     // do not exist for it are fully masked in SM (P = 0, m and l unchanged), Y then adds zeros and
     // X computes scores nobody reads, so one straight-line body serves every k.  The first PREFETCH
     // fragments arrive in `carry` (read during the previous stage) and the last slots read the next
     // stage's first fragments into it, so no stage starts with an empty LDS pipeline.
-    auto stage = [&](auto BLKC, int k, const int (&k_it)[KS], const int (&v_it)[DB], int kdelta, int vdelta,
-                     i32x4_t (&carry)[PREFETCH], f32x16_t (&s_cur)[QH], f32x16_t (&s_nxt)[QH],
+    auto stage = [&](auto BLKC, auto UC, int k, i32x4_t (&carry)[PREFETCH], f32x16_t (&s_cur)[QH], f32x16_t (&s_nxt)[QH],
                      const i32x4_t (&p_in)[QH][2], i32x4_t (&p_out)[QH][2], auto&& side) {
         constexpr int BLK = decltype(BLKC)::value;
         // s_cur was written by the asm MFMAs at the end of the previous stage: keep every vector
@@ -809,10 +834,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         auto issue = [&](auto F) {
             constexpr int f = decltype(F)::value;
             if constexpr (f < NF) {
-                frag[f] = load_frag(F, std::integral_constant<int, BLK>{}, std::false_type{}, k_it, v_it, 0, 0);
+                frag[f] = load_frag(F, std::integral_constant<int, BLK>{}, std::false_type{}, UC);
             } else {
                 carry[f - NF] = load_frag(std::integral_constant<int, f - NF>{}, std::integral_constant<int, BLK ^ 1>{},
-                                          std::integral_constant<bool, BLK == 1>{}, k_it, v_it, kdelta, vdelta);
+                                          std::integral_constant<bool, BLK == 1>{}, UC);
             }
         };
         float psum[QH], pe[QH][16];  // this block's row sums (per lane: its 16 of the 32 keys) and exponentials
@@ -934,21 +959,33 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     };
 
     // ---- prologue: the first LA K tiles and LA-1 V tiles ----
+    // V tile 0 also goes to the last V buffer: the empty first stage multiplies "V tile -1" from there
+    // by P = 0, which needs finite data; the real owner of that buffer is loaded after that stage.
+    {
+        int v_first[LD_PER_W];
+#pragma unroll
+        for (int i = 0; i < LD_PER_W; ++i)
+            v_first[i] = v_goff[i];
+        const TileLoad tv = tile_load(vg, p.v_rs, v_lds, 0, NBUF - 1, v_first, v_goff_last);
+#pragma unroll
+        for (int i = 0; i < LD_PER_W; ++i)
+            issue_load(tv, i, v_first);
+    }
 #pragma unroll
     for (int t = 0; t < LA; ++t)
     {
-        const TileLoad tk = tile_load(kg, p.k_rs, k_lds, t);
+        const TileLoad tk = tile_load(kg, p.k_rs, k_lds, t, t, k_goff, k_goff_last);
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i)
-            issue_load(tk, i, k_goff, k_goff_last);
+            issue_load(tk, i, k_goff);
     }
 #pragma unroll
     for (int t = 0; t + 1 < LA; ++t)
     {
-        const TileLoad tv = tile_load(vg, p.v_rs, v_lds, t);
+        const TileLoad tv = tile_load(vg, p.v_rs, v_lds, t, t, v_goff, v_goff_last);
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i)
-            issue_load(tv, i, v_goff, v_goff_last);
+            issue_load(tv, i, v_goff);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -970,31 +1007,29 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         }
     }
 
-    int k_it[KS], v_it[DB];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        k_it[ks] = k_lane[ks] + (int)k_lds;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-        v_it[db] = v_lane[db] + (int)v_lds;
     i32x4_t carry[PREFETCH];  // first fragments of the coming stage
     static_for<0, PREFETCH>([&](auto F) {
-        carry[decltype(F)::value] = load_frag(F, std::integral_constant<int, 0>{}, std::false_type{}, k_it, v_it, 0, 0);
+        carry[decltype(F)::value] =
+            load_frag(F, std::integral_constant<int, 0>{}, std::false_type{}, std::integral_constant<int, 0>{});
     });
 
-    for (int j = 0; j < niter; ++j) {
+    // One iteration of the key loop: K tile j, V tile j-1.  UC = j mod NBUF as a constant: the loop is
+    // unrolled NBUF times so that every LDS buffer offset is an immediate.
+    auto iteration = [&](auto UC, int j) {
+        constexpr int U = decltype(UC)::value;
         // tiles LA iterations ahead (iteration j reads K tile j and V tile j-1)
         // The 2*LD_PER_W loads of a wavefront are dealt out over the MFMA slots of one stage (even
         // wavefronts: the first stage, odd ones: the second) rather than issued in one burst by all
         // wavefronts right after the barrier, which backs up the memory pipeline and stalls them.
-        const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA), vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1);
+        const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA, (U + LA) % NBUF, k_goff, k_goff_last);
+        const TileLoad vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1, (U + LA - 1) % NBUF, v_goff, v_goff_last);
         if constexpr (!(ABL & 8) && NAUT_SPREAD == 0) {
 #pragma unroll
             for (int i = 0; i < LD_PER_W; ++i)
-                issue_load(kt, i, k_goff, k_goff_last);
+                issue_load(kt, i, k_goff);
 #pragma unroll
             for (int i = 0; i < LD_PER_W; ++i)
-                issue_load(vt, i, v_goff, v_goff_last);
+                issue_load(vt, i, v_goff);
         }
         auto side = [&](auto BLKC, auto I) {
             constexpr int BLK = decltype(BLKC)::value, i = decltype(I)::value;
@@ -1003,32 +1038,19 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 constexpr int q = i / STEP;
                 if (NAUT_SPREAD == 1 ? BLK == 0 : (wave & 1) == BLK) {
                     if constexpr (q < LD_PER_W)
-                        issue_load(kt, q, k_goff, k_goff_last);
+                        issue_load(kt, q, k_goff);
                     else
-                        issue_load(vt, q - LD_PER_W, v_goff, v_goff_last);
+                        issue_load(vt, q - LD_PER_W, v_goff);
                 }
             }
         };
 
-        // LDS addresses of this iteration's tiles; the next iteration's differ by a scalar
-        const int kdelta = (((j + 1) % NBUF) - (j % NBUF)) * TILEB;
-        const int vdelta = ((j % NBUF) - ((j > 0 ? j - 1 : 0) % NBUF)) * TILEB;
         // stage 2j-1: Y(2j-2) with p_e, X(2j) -> s_e, SM(2j-1): s_o -> p_o
-        stage(std::integral_constant<int, 0>{}, 2 * j - 1, k_it, v_it, kdelta, vdelta, carry, s_o, s_e, p_e, p_o,
+        stage(std::integral_constant<int, 0>{}, UC, 2 * j - 1, carry, s_o, s_e, p_e, p_o,
               [&](auto I) { side(std::integral_constant<int, 0>{}, I); });
         // stage 2j:   Y(2j-1) with p_o, X(2j+1) -> s_o, SM(2j): s_e -> p_e
-        stage(std::integral_constant<int, 1>{}, 2 * j, k_it, v_it, kdelta, vdelta, carry, s_e, s_o, p_o, p_e,
+        stage(std::integral_constant<int, 1>{}, UC, 2 * j, carry, s_e, s_o, p_o, p_e,
               [&](auto I) { side(std::integral_constant<int, 1>{}, I); });
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            k_it[ks] += kdelta;
-            asm volatile("" : "+v"(k_it[ks]));  // one add per tile, not one per LDS read
-        }
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            v_it[db] += vdelta;
-            asm volatile("" : "+v"(v_it[db]));
-        }
 
         // The last slots of the next iteration already read the tiles of the one after it, so the
         // tiles issued LA-2 iterations ago must have landed by now; newer ones may fly on.
@@ -1042,6 +1064,13 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // been awaited just above.
         if constexpr (!(ABL & 4))
             asm volatile("s_barrier" ::: "memory");
+    };
+    for (int j0 = 0; j0 < niter; j0 += NBUF) {
+        static_for<0, NBUF>([&](auto UC) {
+            const int j = j0 + decltype(UC)::value;
+            if (j < niter)  // uniform over the work-group
+                iteration(UC, j);
+        });
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if constexpr ((ABL & 64) != 0) {
