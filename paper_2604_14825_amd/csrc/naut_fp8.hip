@@ -27,6 +27,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <type_traits>
 
 #include "naut_attn.h"
 #include "naut_common.h"
@@ -133,27 +134,61 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     const int kv_end = CAUSAL ? (S < (qt + 1) * F8_BM ? S : (qt + 1) * F8_BM) : S;
     const int ntiles = (kv_end + F8_BN - 1) / F8_BN;
 
+    // Register-staged tile loads.  Per-thread byte offsets inside a tile are fixed; the tile's base is
+    // wave-uniform, so a load is a scalar base plus a 32-bit lane offset.  Only the last tile of the
+    // sequence can be ragged: it takes a second set of offsets that re-read the last row, chosen by a
+    // uniform branch.  LDS store addresses are fixed too (the buffer offset is an immediate, the loop
+    // below is unrolled over the two buffers).
     i32x4_t kst[LD_PER_T], vst[LD_PER_T];
-    auto g_load = [&](int tile) {
-#pragma unroll
-        for (int i = 0; i < LD_PER_T; ++i) {
-            const int L = tid + F8_THREADS * i;
-            int row = tile * F8_BN + L / CPR16;
-            row = row < S ? row : S - 1;
-            const size_t off = (size_t)row * D + (L % CPR16) * 16;
-            kst[i] = *(const i32x4_t*)(kg + off);
-            vst[i] = *(const i32x4_t*)(vg + off);
-        }
-    };
-    auto s_store = [&](int buf) {
-        unsigned char* kt = smem + buf * 2 * TILEB;
-        unsigned char* vt = kt + TILEB;
+    int g_off[LD_PER_T], g_off_last[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
+    {
+        const int s_tiles = (S + F8_BN - 1) / F8_BN;
+        const int rows_left = S - (s_tiles - 1) * F8_BN;  // rows of the sequence's last tile, >= 1
 #pragma unroll
         for (int i = 0; i < LD_PER_T; ++i) {
             const int L = tid + F8_THREADS * i;
             const int row = L / CPR16, c16 = L % CPR16;
-            *(i32x4_t*)(kt + k8_off<D>(row, c16)) = kst[i];
-            *(i32x4_t*)(vt + v8_off<D>(row, c16 >> 1) + (c16 & 1) * 16) = vst[i];
+            g_off[i] = row * D + c16 * 16;
+            g_off_last[i] = (row < rows_left ? row : rows_left - 1) * D + c16 * 16;
+            st_k[i] = k8_off<D>(row, c16);
+            st_v[i] = v8_off<D>(row, c16 >> 1) + (c16 & 1) * 16;
+        }
+    }
+    const int last_tile = (S + F8_BN - 1) / F8_BN - 1;
+    auto g_load = [&](int tile) {
+        // the tile offset is pinned in scalar registers: otherwise it is folded into 64-bit per-lane
+        // addresses computed with vector instructions for every load
+        size_t toff = (size_t)tile * TILEB;
+        asm volatile("" : "+s"(toff));
+        const unsigned char* kp = kg + toff;
+        const unsigned char* vp = vg + toff;
+        if (tile == last_tile) {
+#pragma unroll
+            for (int i = 0; i < LD_PER_T; ++i) {
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)g_off_last[i]);
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)g_off_last[i]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LD_PER_T; ++i) {
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)g_off[i]);
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)g_off[i]);
+            }
+        }
+    };
+    const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
+#pragma unroll
+    for (int i = 0; i < LD_PER_T; ++i) {
+        st_k[i] += (int)smem_base;
+        st_v[i] += (int)smem_base;
+        asm volatile("" : "+v"(st_k[i]), "+v"(st_v[i]));  // opaque: buffer offsets stay instruction immediates
+    }
+    auto s_store = [&](auto BUFC) {
+        constexpr int KB_OFF = decltype(BUFC)::value * 2 * TILEB;
+#pragma unroll
+        for (int i = 0; i < LD_PER_T; ++i) {
+            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_k[i] + KB_OFF) = kst[i];
+            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_v[i] + KB_OFF + TILEB) = vst[i];
         }
     };
 
@@ -162,6 +197,22 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     const int v_e = i16 >> 1;                                      // which of the 8 keys of a read this lane addresses
     const int v_key = 4 * h + (v_e & 3) + ((v_e >> 2) << 3);       // + base(t): keys {0,1,2,3,8,9,10,11} + 4h
     const int v_byte = 16 * ((lane >> 4) & 1) + 8 * (i16 & 1);     // inside the 32-byte chunk of block db
+    // fixed LDS addresses of this lane's fragment reads in buffer 0 (K: per k-step and 16-byte half; V:
+    // per 32-row block of O^T and group of 8 keys); buffer and key-block offsets are immediates
+    int rd_k[KS][2], rd_v[DB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            rd_k[ks][u] = (int)smem_base + k8_off<D>(l32, ks * 4 + h * 2 + u);
+            asm volatile("" : "+v"(rd_k[ks][u]));
+        }
+    // (adding 16 or 32 to a row changes neither swizzle key, so those steps are plain byte offsets)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        rd_v[db] = (int)smem_base + v8_off<D>(v_key, db) + v_byte;
+        asm volatile("" : "+v"(rd_v[db]));
+    }
 
     f32x16_t oacc[DB];
 #pragma unroll
@@ -173,13 +224,13 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     float l_run = 0.f;
 
     g_load(0);
-    s_store(0);
+    s_store(std::integral_constant<int, 0>{});
     __syncthreads();
 
-    for (int j = 0; j < ntiles; ++j) {
-        const int buf = j & 1;
-        const unsigned char* kt = smem + buf * 2 * TILEB;
-        const unsigned char* vt = kt + TILEB;
+    // one key tile; BUFC = j & 1 as a constant (the driver loop below alternates the two instances)
+    auto step = [&](auto BUFC, int j) {
+        constexpr int BUF = decltype(BUFC)::value;
+        constexpr int KT = BUF * 2 * TILEB, VT = KT + TILEB;  // byte offsets of this step's K and V tiles
         const int kv0 = j * F8_BN;
         if (j + 1 < ntiles)
             g_load(j + 1);
@@ -194,9 +245,8 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
                     sacc[kb][r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const int row = kb * 32 + l32, c0 = ks * 4 + h * 2;
-                    const i32x4_t lo = *(const i32x4_t*)(kt + k8_off<D>(row, c0));
-                    const i32x4_t hi = *(const i32x4_t*)(kt + k8_off<D>(row, c0 + 1));
+                    const i32x4_t lo = *(const NAUT_LDS i32x4_t*)(uintptr_t)(rd_k[ks][0] + KT + kb * 32 * D);
+                    const i32x4_t hi = *(const NAUT_LDS i32x4_t*)(uintptr_t)(rd_k[ks][1] + KT + kb * 32 * D);
                     const i32x8_t kf = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                     sacc[kb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[ks], sacc[kb], 0, 0, 0, 0, 0, 0);
                 }
@@ -255,9 +305,8 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
                 i32x8_t vf;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const int key = 32 * (t >> 1) + 16 * (t & 1) + v_key;
                     const i32x2_t x = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                        (NAUT_LDS i32x2_t*)(vt + v8_off<D>(key, db) + v_byte));
+                        (NAUT_LDS i32x2_t*)(uintptr_t)(rd_v[db] + VT + (32 * (t >> 1) + 16 * (t & 1)) * D));
                     vf[2 * t] = x.x;
                     vf[2 * t + 1] = x.y;
                 }
@@ -265,8 +314,13 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
             }
         }
         if (j + 1 < ntiles)
-            s_store(buf ^ 1);
+            s_store(std::integral_constant<int, BUF ^ 1>{});
         __syncthreads();
+    };
+    for (int j = 0; j < ntiles; j += 2) {
+        step(std::integral_constant<int, 0>{}, j);
+        if (j + 1 < ntiles)
+            step(std::integral_constant<int, 1>{}, j + 1);
     }
 
     // Epilogue: one division by l (the 2^7 of P cancels), times descale_v; lse undoes the shift.
