@@ -66,6 +66,15 @@ struct Params {
     int cpr;       // real 16-byte chunks per row = head dimension / 8
 };
 
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 // S^T MFMAs of the variants that need more than 256 registers per lane (64 queries per wavefront in
 // kernel 2, D = 256 in kernel 1), written as asm so that their accumulator is an ordinary vector
 // register tuple while O and Q live in the accumulation registers (the compiler's own MFMA form
@@ -233,29 +242,77 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
 
-    // D <= 128: global -> register staging of one K and one V tile
+    // D <= 128: global -> register staging of one K and one V tile.  A load is a wave-uniform tile base
+    // plus a fixed 32-bit lane offset; the last tile of the sequence, which may be ragged, has offsets of
+    // its own that re-read the last row (chosen by a uniform branch).  LDS store addresses are fixed
+    // registers plus the buffer offset as an immediate (the key loop is unrolled over the buffers).
     i32x4_t kst[LD_PER_T], vst[LD_PER_T];
+    int gk_off[LD_PER_T], gv_off[LD_PER_T], gk_last[LD_PER_T], gv_last[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
+    const int last_tile = (S + BN - 1) / BN - 1;
+    if constexpr (!WIDE) {
+        const int rows_left = S - last_tile * BN;  // rows of the sequence's last tile, >= 1
+#pragma unroll
+        for (int i = 0; i < LD_PER_T; ++i) {
+            const int L = tid + NTHREADS * i;
+            const int row = L / CPR, rl = row < rows_left ? row : rows_left - 1;
+            const int ch = (L % CPR < cpr ? L % CPR : cpr - 1) * 16;
+            gk_off[i] = row * p.k_rs + ch;
+            gv_off[i] = row * p.v_rs + ch;
+            gk_last[i] = rl * p.k_rs + ch;
+            gv_last[i] = rl * p.v_rs + ch;
+            st_k[i] = (int)smem_base + k_off<D>(row, L % CPR);
+            st_v[i] = (int)smem_base + v_off<D>(row, L % CPR);
+            asm volatile("" : "+v"(st_k[i]), "+v"(st_v[i]));  // opaque: buffer offsets stay instruction immediates
+        }
+    }
     auto g_load = [&](int tile) {
+        // tile offsets pinned in scalar registers: otherwise they are folded into 64-bit per-lane
+        // addresses computed with vector instructions for every load
+        size_t koff = (size_t)tile * BN * p.k_rs, voff = (size_t)tile * BN * p.v_rs;
+        asm volatile("" : "+s"(koff), "+s"(voff));
+        const unsigned char* kp = kg + koff;
+        const unsigned char* vp = vg + voff;
+        if (tile == last_tile) {
 #pragma unroll
-        for (int i = 0; i < LD_PER_T; ++i) {
-            const int L = tid + NTHREADS * i;
-            int row = tile * BN + L / CPR;
-            row = row < S ? row : S - 1;
-            const int ch = L % CPR < cpr ? L % CPR : cpr - 1;
-            kst[i] = *(const i32x4_t*)(kg + (size_t)row * p.k_rs + ch * 16);
-            vst[i] = *(const i32x4_t*)(vg + (size_t)row * p.v_rs + ch * 16);
+            for (int i = 0; i < LD_PER_T; ++i) {
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)gk_last[i]);
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)gv_last[i]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LD_PER_T; ++i) {
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)gk_off[i]);
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)gv_off[i]);
+            }
         }
     };
-    auto s_store = [&](int buf) {
-        unsigned char* kt = smem + buf * 2 * TILEB;
-        unsigned char* vt = kt + TILEB;
+    auto s_store = [&](auto BUFC) {
+        constexpr int OFF = decltype(BUFC)::value * 2 * TILEB;
 #pragma unroll
         for (int i = 0; i < LD_PER_T; ++i) {
-            const int L = tid + NTHREADS * i;
-            *(i32x4_t*)(kt + k_off<D>(L / CPR, L % CPR)) = kst[i];
-            *(i32x4_t*)(vt + v_off<D>(L / CPR, L % CPR)) = vst[i];
+            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_k[i] + OFF) = kst[i];
+            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_v[i] + OFF + TILEB) = vst[i];
         }
     };
+    // fixed LDS addresses of this lane's fragment reads in buffer 0 (K: per k-step; V: per 32-row block
+    // of O^T, first of the two transposed reads); buffer, key-block and key-step offsets are immediates
+    // (adding 8, 16 or 32 to a row changes no swizzle key)
+    int rd_k[KS], rd_v[DB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        rd_k[ks] = (int)smem_base + k_off<D>(l32, ks * 2 + h);
+        asm volatile("" : "+v"(rd_k[ks]));
+    }
+    {
+        const int i16 = lane & 15;
+        const int key = 4 * h + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int d = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+            rd_v[db] = (int)smem_base + v_off<D>(key, d >> 3) + (d & 7) * 2;
+            asm volatile("" : "+v"(rd_v[db]));
+        }
+    }
 
     f32x16_t oacc[DB];
 #pragma unroll
@@ -277,14 +334,18 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         asm volatile("s_barrier" ::: "memory");
     } else {
         g_load(0);
-        s_store(0);
+        s_store(std::integral_constant<int, 0>{});
         __syncthreads();
     }
 
-    for (int j = 0; j < ntiles; ++j) {
-        const int buf = j & 1;
-        const unsigned char* kt = WIDE ? smem + (j % NB) * TILEB : smem + buf * 2 * TILEB;
-        const unsigned char* vt = WIDE ? kt + NB * TILEB : kt + TILEB;
+    // One key tile.  D <= 128: UC = j & 1 as a constant -- the driver loop below is unrolled over the two
+    // LDS buffers, so the tile's LDS offsets are immediates.  D = 256 keeps one copy of its (long) body
+    // and adds the buffer offset at run time.
+    constexpr int NU = WIDE ? 1 : 2;
+    auto step = [&](auto UC, int j) {
+        constexpr int U = decltype(UC)::value;
+        const int KT = WIDE ? (j % NB) * TILEB : U * 2 * TILEB;   // byte offset of this step's K tile
+        const int VT = WIDE ? KT + NB * TILEB : KT + TILEB;
         const int kv0 = j * BN;
         if constexpr (WIDE) {
             // buffer (j + NB - 1) % NB was last read in step j - 1, which every wavefront has left
@@ -308,11 +369,11 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                     i32x4_t kf[KS];
 #pragma unroll
                     for (int ks = 0; ks < KPF; ++ks)
-                        kf[ks] = *(const i32x4_t*)(kt + k_off<D>(kb * 32 + l32, ks * 2 + h));
+                        kf[ks] = *(const NAUT_LDS i32x4_t*)(uintptr_t)(rd_k[ks] + KT + kb * 32 * ROWB);
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
                         if (ks + KPF < KS)
-                            kf[ks + KPF] = *(const i32x4_t*)(kt + k_off<D>(kb * 32 + l32, (ks + KPF) * 2 + h));
+                            kf[ks + KPF] = *(const NAUT_LDS i32x4_t*)(uintptr_t)(rd_k[ks + KPF] + KT + kb * 32 * ROWB);
                         if (ks == 0)
                             XMfma<DT_IN>::first(sacc[kb], kf[ks], qf[ks]);
                         else
@@ -325,7 +386,7 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                         sacc[kb][r] = 0.f;
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        const i32x4_t kf = *(const i32x4_t*)(kt + k_off<D>(kb * 32 + l32, ks * 2 + h));
+                        const i32x4_t kf = *(const NAUT_LDS i32x4_t*)(uintptr_t)(rd_k[ks] + KT + kb * 32 * ROWB);
                         sacc[kb] = T::mfma(kf, qf[ks], sacc[kb]);
                     }
                 }
@@ -391,7 +452,11 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                               T::pack2(sacc[kb][r0 + 4], sacc[kb][r0 + 5]), T::pack2(sacc[kb][r0 + 6], sacc[kb][r0 + 7])};
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const i32x4_t vf = load_vt_frag<D>(vt, t * 16, db, lane);
+                    const int a = rd_v[db] + VT + t * 16 * ROWB;
+                    const i16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)a);
+                    const i16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((NAUT_LDS i16x4_t*)(uintptr_t)(a + 8 * ROWB));
+                    const i32x2_t lo = __builtin_bit_cast(i32x2_t, r0), hi = __builtin_bit_cast(i32x2_t, r1);
+                    const i32x4_t vf = {lo.x, lo.y, hi.x, hi.y};
                     oacc[db] = T::mfma(vf, pb, oacc[db]);
                 }
             }
@@ -404,9 +469,16 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             asm volatile("s_barrier" ::: "memory");
         } else {
             if (j + 1 < ntiles)
-                s_store(buf ^ 1);
+                s_store(std::integral_constant<int, U ^ 1>{});
             __syncthreads();
         }
+    };
+    for (int j0 = 0; j0 < ntiles; j0 += NU) {
+        static_for<0, NU>([&](auto UC) {
+            const int j = j0 + decltype(UC)::value;
+            if (j < ntiles)  // uniform over the work-group
+                step(UC, j);
+        });
     }
 
     // Epilogue: one division by l (the per-step divide/multiply pairs telescope away), lse, store.
@@ -480,15 +552,6 @@ constexpr int BM2 = 256;
 constexpr int LA = NAUT_LA;     // tile loads are issued this many iterations ahead of their use
 constexpr int NBUF = LA + 1;    // LDS buffers per operand
 constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no maximum yet": keeps -inf - (-inf) out
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
 
 // sum over the two 32-lane halves (same exchange as half_max)
 __device__ __forceinline__ float half_sum(float x)
