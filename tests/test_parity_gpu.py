@@ -28,6 +28,8 @@ SMALL = [
     (1, 8, 2, 400, 128, True, synth.BF16, synth.F32),
     (1, 2, 2, 512, 128, True, synth.BF16, synth.BF16),
     (1, 2, 1, 777, 128, False, synth.BF16, synth.BF16),
+    (1, 4, 2, 300, 256, True, synth.BF16, synth.BF16),    # the widest head dimension through the dense entry point
+    (2, 2, 2, 33, 256, False, synth.F16, synth.F32),
 ]
 
 
@@ -86,6 +88,23 @@ def test_moving_reference_maximum(kind, variant, monkeypatch):
         o, lse = gu.run_hip(q, k, v, idt, odt, causal2, 4.0 * scale)  # hotter softmax: scores in the hundreds
         o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal2, 4.0 * scale)
         gu.check(o, lse, o_ref, lse_ref, kind + "/" + variant + "/hot")
+
+
+@pytest.mark.parametrize("kind", ["ascending", "descending", "late_spike"])
+def test_moving_reference_maximum_wide(kind):
+    """The same score profiles on the D = 256 kernel, whose rescale block moves O between register files."""
+    B, Hq, Hkv, S, D, idt, odt = 1, 4, 2, 500, 256, synth.BF16, synth.F32
+    seed = 4343
+    q = synth.fill(B, Hq, S, D, seed, synth.TAG_Q, idt)
+    k = synth.fill(B, Hkv, S, D, seed, synth.TAG_K, idt)
+    v = synth.fill(B, Hkv, S, D, seed, synth.TAG_V, idt)
+    k = synth.round16(_bits_to_f32(k, idt) * _key_profile(kind, S)[None, None, :, None], idt)
+    scale = 1.0 / math.sqrt(D)
+    print("case wide", kind, flush=True)
+    for causal, sc in ((True, scale), (False, 4.0 * scale)):
+        o, lse = gu.run_hip(q, k, v, idt, odt, causal, sc)
+        o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal, sc)
+        gu.check(o, lse, o_ref, lse_ref, "wide/" + kind)
 
 
 VARIANT_SHAPES = [
