@@ -707,6 +707,11 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     const int kv_end_w = Q0 >= S ? 0 : (CAUSAL ? (S < Q0 + WQ ? S : Q0 + WQ) : S);
     const int ntiles = (kv_end_wg + BN - 1) / BN;
     const int niter = ntiles + 1;  // stages -1 .. 2*ntiles, two per iteration
+    // With the causal mask the wavefronts of a work-group finish at different keys: this one needs blocks
+    // up to kw_last, i.e. stages up to kw_last + 1 = iterations below n_act; after those it only keeps
+    // loading its share of the tiles (the others still read them) and meeting the barrier.
+    const int kw_last = (kv_end_w + 31) / 32 - 1;
+    const int n_act = CAUSAL ? ((kw_last + 2) / 2 + 1 < niter ? (kw_last + 2) / 2 + 1 : niter) : niter;
 
     // Direct global->LDS tile loads.  Each instruction moves 1 KB: lane i fills physical chunk i of
     // the block, so the lane fetches the logical chunk that the swizzle maps there.  The address is
@@ -1143,12 +1148,28 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         if constexpr (!(ABL & 4))
             asm volatile("s_barrier" ::: "memory");
     };
-    for (int j0 = 0; j0 < niter; j0 += NBUF) {
+    for (int j0 = 0; j0 < n_act; j0 += NBUF) {
         static_for<0, NBUF>([&](auto UC) {
             const int j = j0 + decltype(UC)::value;
-            if (j < niter)  // uniform over the work-group
+            if (j < n_act)  // uniform over the wavefront
                 iteration(UC, j);
         });
+    }
+    for (int j = n_act; j < niter; ++j) {  // this wavefront's part of the remaining tiles, one barrier each
+        const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA, (j + LA) % NBUF, k_goff, k_goff_last);
+        const TileLoad vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1, (j + LA - 1) % NBUF, v_goff, v_goff_last);
+        if constexpr (!(ABL & 8)) {
+#pragma unroll
+            for (int i = 0; i < LD_PER_W; ++i)
+                issue_load(kt, i, k_goff);
+#pragma unroll
+            for (int i = 0; i < LD_PER_W; ++i)
+                issue_load(vt, i, v_goff);
+        }
+        if constexpr (!(ABL & 256))
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
+        if constexpr (!(ABL & 4))
+            asm volatile("s_barrier" ::: "memory");
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if constexpr ((ABL & 64) != 0) {
