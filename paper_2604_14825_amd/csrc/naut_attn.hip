@@ -1,7 +1,10 @@
 // naut_attn.hip -- fused attention forward for gfx950 (MI355X) and its C ABI.
 //
 // One kernel computes O = softmax(scale * Q K^T + causal mask) V for a
-// (batch, head, 128-query tile) per work-group.  The reductions over the key
+// (batch, head, query tile) per work-group; three variants share the formulation
+// below and are picked per shape (pick_variant): kernel 1 (128 queries per
+// work-group; also the D = 256 instantiation) and kernel 2 (256 queries,
+// software-pipelined over 32-key blocks, in two shapes).  The reductions over the key
 // axis (row max, row sum, weighted sum of V) are fused with the rolling-update
 // scheme of Section 4.2/4.3 of the paper: a running maximum m and running sum l
 // are kept per query, and whenever m grows the partial results are repaired by
@@ -11,8 +14,8 @@
 // one per step.
 //
 // Work decomposition (bi-level tiling, Section 4.2): outer loops (batch, head,
-// query tile) -> work-groups; inner tile = 128 queries x 64 keys.  A work-group
-// has 4 wavefronts, each owning 32 queries.  Per key tile and wavefront:
+// query tile) -> work-groups; inner tile = 128 or 256 queries x 64 keys.  A
+// wavefront owns 32 (or 64) queries.  Per key tile and wavefront:
 //
 //   S^T[key][query] = K_tile . Q^T     v_mfma_f32_32x32x16 (A = K from LDS, B = Q in registers)
 //   online softmax over keys           each lane owns ONE query (column) and 16 keys per 32-key block,
@@ -22,8 +25,9 @@
 //                                      S^T accumulator registers (no shuffle: the MFMA k-slot <-> key
 //                                      assignment is chosen to match the accumulator layout)
 //
-// K and V tiles are double-buffered in LDS (global -> registers -> LDS, one
-// barrier per step).
+// K and V tiles are multi-buffered in LDS, one barrier per tile: kernel 1 stages
+// them through registers (two buffers), kernel 2 and the D = 256 instantiation load
+// them straight from global memory into LDS several tiles ahead (four buffers).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
