@@ -7,7 +7,15 @@ import sys
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SRCS = [os.path.join(_HERE, "csrc", n) for n in ("naut_attn.hip", "naut_decode.hip", "naut_fp8.hip")]
+_CSRC = os.path.join(_HERE, "csrc")
+# (source, extra defines, object name).  The prefill kernels are instantiated in naut_attn_inst.hip, compiled
+# once per (input type, output type) pair so that the four pairs build in parallel.
+_DT = {"bf16": 0, "f16": 1, "f32": 2}  # naut_dtype
+JOBS = [(os.path.join(_CSRC, n), [], n + ".o") for n in ("naut_attn.hip", "naut_decode.hip", "naut_fp8.hip")]
+JOBS += [(os.path.join(_CSRC, "naut_attn_inst.hip"), ["-DNAUT_INST_IN=%d" % _DT[i], "-DNAUT_INST_OUT=%d" % _DT[o]],
+          "naut_attn_inst_%s_%s.o" % (i, o))
+         for i, o in (("bf16", "bf16"), ("bf16", "f32"), ("f16", "f16"), ("f16", "f32"))]
+SRCS = sorted({j[0] for j in JOBS})
 LIB = os.path.join(_HERE, "libnaut_attn.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -23,14 +31,32 @@ FLAGS = [
 ]
 
 
-def build_lib(extra=(), verbose=False) -> str:
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + list(extra) + SRCS + ["-o", tmp]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+def build_lib(extra=(), verbose=False, out=None) -> str:
+    """Compile every translation unit to an object (in parallel: one hipcc each), then link the shared
+    library (to `out` if given, else in place)."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    out = out or LIB
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="naut_build_") as tmpdir:
+        objs = [os.path.join(tmpdir, j[2]) for j in JOBS]
+
+        def compile_one(job):
+            (src, defs, _), obj = job
+            cmd = [HIPCC] + compile_flags + list(extra) + defs + ["-c", src, "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.check_call(cmd)
+
+        with ThreadPoolExecutor(max_workers=min(len(JOBS), os.cpu_count() or 1)) as pool:
+            list(pool.map(compile_one, zip(JOBS, objs)))
+        tmp = out + ".tmp%d" % os.getpid()
+        link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.check_call(link)
+        os.replace(tmp, out)
+    return out
 
 
 def build_all(verbose=False):
@@ -43,4 +69,8 @@ if __name__ == "__main__":
     sys.path.insert(0, ROOT)
     from paper_2604_14825_amd import synth
     synth.build(force=True)
-    print(build_lib(extra=sys.argv[1:], verbose=True))
+    args = sys.argv[1:]
+    out = None
+    if args and args[0].startswith("--out="):  # link somewhere else (A/B builds with extra -D flags)
+        out, args = args[0][len("--out="):], args[1:]
+    print(build_lib(extra=args, verbose=True, out=out))

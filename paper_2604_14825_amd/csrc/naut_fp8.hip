@@ -20,7 +20,7 @@
 //     2^-9): with the reference maximum at most one binade below the true one P*2^7 <= 256 < 448, and
 //     the factor cancels in O / l.  The conversion does not saturate (it makes NaN), hence the bound.
 //
-// Work decomposition as the 128-query kernel of naut_attn.hip: 4 wavefronts x 32 queries per
+// Work decomposition as the 128-query kernel of naut_attn_kernels.h: 4 wavefronts x 32 queries per
 // work-group, 64-key tiles, register-staged loads, double-buffered LDS, one barrier per tile.
 #include <hip/hip_runtime.h>
 
