@@ -576,6 +576,7 @@ constexpr int ABL = NAUT_ABLATE;  // timing experiments only (results are wrong 
 constexpr int HEADS_AT_ONCE = NAUT_HAO;
 constexpr int BM2 = 256;
 constexpr int LA = NAUT_LA;     // tile loads are issued this many iterations ahead of their use
+static_assert(LA == 3, "3 is the depth the unrolled key loop has been validated and measured with");
 constexpr int NBUF = LA + 1;    // LDS buffers per operand
 constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no maximum yet": keeps -inf - (-inf) out
 
