@@ -77,9 +77,12 @@ __device__ __forceinline__ int v8_off(int row, int c32)
     return row * D + ((c32 ^ key) << 5);
 }
 
-__device__ __forceinline__ int pack4_fp8(float x0, float x1, float x2, float x3)
+// Four floats to four E4M3 bytes.  The conversion writes one 16-bit half of its destination and keeps the
+// other; `old` is whatever the register held (both halves get written, so it only saves the instruction
+// that would clear it).
+__device__ __forceinline__ int pack4_fp8(float x0, float x1, float x2, float x3, int old)
 {
-    int w = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+    const int w = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, old, false);
     return __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, w, true);
 }
 
@@ -222,6 +225,7 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
             oacc[db][r] = 0.f;
     float m_run = F8_M_INIT;
     float l_run = 0.f;
+    i32x8_t pb = {0, 0, 0, 0, 0, 0, 0, 0};  // P of the current tile as the B operand (lives across tiles, see pack4_fp8)
 
     g_load(0);
     s_store(std::integral_constant<int, 0>{});
@@ -293,11 +297,10 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
                 }
             l_run += psum;
             // P as the B operand: k-slot 16*kb + r of this lane half is score register r of block kb
-            i32x8_t pb;
 #pragma unroll
             for (int w = 0; w < 8; ++w) {
                 const int kb = w >> 2, r0 = (w & 3) * 4;
-                pb[w] = pack4_fp8(sacc[kb][r0 + 0], sacc[kb][r0 + 1], sacc[kb][r0 + 2], sacc[kb][r0 + 3]);
+                pb[w] = pack4_fp8(sacc[kb][r0 + 0], sacc[kb][r0 + 1], sacc[kb][r0 + 2], sacc[kb][r0 + 3], pb[w]);
             }
             // O^T += V^T . P^T, all 64 keys of the tile in one MFMA per 32 rows of O^T
 #pragma unroll
