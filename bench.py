@@ -33,7 +33,7 @@ MEASURED_TRAFFIC_BYTES = {
     "long": 1.607e9,
     # profiles/naut_decode_B8_Hq32_Hkv8_Sk16384_D128.md: (262347 + 407) KiB x 2.000 read + (528 + 72) KiB written
     "decode": 5.387e8,
-    # profiles/naut_fwd_fp8_long_S16384_D128_causal.md: 564460 KiB x 2.000 read + 133123 KiB written
+    # profiles/naut_fwd_fp8_long_S16384_D128_causal.md: 564080 KiB x 2.000 read + 133170 KiB written
     "long_fp8": 1.292e9,
     # profiles/naut_fwd_bm128_w4q32_bn32_long_S16384_D256_causal.md: 2604500 KiB x 2.000 read + 264190 KiB written
     "long_d256": 5.60e9,
