@@ -117,6 +117,17 @@ int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, floa
                       int B, int Hq, int Hkv, int S, int D, int causal, float scale,
                       float descale_q, float descale_k, float descale_v, void* stream);
 
+/*
+ * The same on strided tensors (e.g. sequence-major [B][S][H][D], the layout FP8 attention is usually fed):
+ * `st` as in naut_attn_fwd_strided, in elements, except that q/k/v strides must be multiples of 16 (their
+ * elements are bytes and rows are read 16 bytes at a time); o is bf16, its strides multiples of 4.  D is 64 or
+ * 128.  st = NULL means contiguous, which is what naut_attn_fwd_fp8 passes.
+ */
+int naut_attn_fwd_fp8_strided(const void* q, const void* k, const void* v, void* o, float* lse,
+                              int B, int Hq, int Hkv, int S, int D, int causal, float scale,
+                              float descale_q, float descale_k, float descale_v, void* stream,
+                              const naut_strides* st);
+
 /* Message for the last non-OK status returned on the calling thread ("" if none). Never NULL. */
 const char* naut_last_error_string(void);
 

@@ -56,6 +56,10 @@ struct Fp8Params {
     int nqt;        // ceil(S / 128)
     float c;        // scale * descale_q * descale_k * log2(e), > 0
     float dv;       // descale_v
+    // byte strides of batch, head and sequence position (the D axis is contiguous; q, k, v: 1 byte per
+    // element, o: 2)
+    long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
+    int q_rs, k_rs, v_rs, o_rs;
 };
 
 // K tile: 64 rows of D bytes; the 16-byte chunks of a row are XOR-ed with (row/2), so that the 32 lanes
@@ -86,7 +90,9 @@ __device__ __forceinline__ int pack4_fp8(float x0, float x1, float x2, float x3,
     return __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, w, true);
 }
 
-template <int D, bool CAUSAL>
+// STRIDED = false: contiguous [B][H][S][D] tensors, every stride a compile-time constant (the launch
+// parameters' strides are not read); true: strides from the launch parameters.
+template <int D, bool CAUSAL, bool STRIDED>
 __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Params p)
 {
     constexpr int TILEB = F8_BN * D;            // bytes per K or V tile
@@ -114,9 +120,13 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     const int S = p.S;
     const float c = p.c;
 
-    const unsigned char* qg = (const unsigned char*)p.q + (size_t)bh * S * D;
-    const unsigned char* kg = (const unsigned char*)p.k + (size_t)(b * p.Hkv + hk) * S * D;
-    const unsigned char* vg = (const unsigned char*)p.v + (size_t)(b * p.Hkv + hk) * S * D;
+    const int q_rs = STRIDED ? p.q_rs : D, k_rs = STRIDED ? p.k_rs : D, v_rs = STRIDED ? p.v_rs : D;
+    const int o_rs = STRIDED ? p.o_rs : D * 2;
+    const unsigned char* qg = (const unsigned char*)p.q + (STRIDED ? b * p.q_bs + hq * p.q_hs : (long long)bh * S * D);
+    const unsigned char* kg =
+        (const unsigned char*)p.k + (STRIDED ? b * p.k_bs + hk * p.k_hs : (long long)(b * p.Hkv + hk) * S * D);
+    const unsigned char* vg =
+        (const unsigned char*)p.v + (STRIDED ? b * p.v_bs + hk * p.v_hs : (long long)(b * p.Hkv + hk) * S * D);
 
     const int q_wave0 = qt * F8_BM + wave * 32;
     const int my_q = q_wave0 + l32;
@@ -126,8 +136,8 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     i32x8_t qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        const i32x4_t lo = *(const i32x4_t*)(qg + (size_t)my_q_ld * D + ks * 64 + h * 32);
-        const i32x4_t hi = *(const i32x4_t*)(qg + (size_t)my_q_ld * D + ks * 64 + h * 32 + 16);
+        const i32x4_t lo = *(const i32x4_t*)(qg + (size_t)my_q_ld * q_rs + ks * 64 + h * 32);
+        const i32x4_t hi = *(const i32x4_t*)(qg + (size_t)my_q_ld * q_rs + ks * 64 + h * 32 + 16);
         qf[ks] = i32x8_t{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     }
 #pragma unroll
@@ -143,39 +153,45 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     // uniform branch.  LDS store addresses are fixed too (the buffer offset is an immediate, the loop
     // below is unrolled over the two buffers).
     i32x4_t kst[LD_PER_T], vst[LD_PER_T];
-    int g_off[LD_PER_T], g_off_last[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
+    int gk_off[LD_PER_T], gv_off[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
     {
-        const int s_tiles = (S + F8_BN - 1) / F8_BN;
-        const int rows_left = S - (s_tiles - 1) * F8_BN;  // rows of the sequence's last tile, >= 1
 #pragma unroll
         for (int i = 0; i < LD_PER_T; ++i) {
             const int L = tid + F8_THREADS * i;
             const int row = L / CPR16, c16 = L % CPR16;
-            g_off[i] = row * D + c16 * 16;
-            g_off_last[i] = (row < rows_left ? row : rows_left - 1) * D + c16 * 16;
+            gk_off[i] = row * k_rs + c16 * 16;
+            gv_off[i] = row * v_rs + c16 * 16;
             st_k[i] = k8_off<D>(row, c16);
             st_v[i] = v8_off<D>(row, c16 >> 1) + (c16 & 1) * 16;
         }
     }
     const int last_tile = (S + F8_BN - 1) / F8_BN - 1;
+    const int rows_last = S - last_tile * F8_BN;  // rows of the sequence's last tile, >= 1
     auto g_load = [&](int tile) {
         // the tile offset is pinned in scalar registers: otherwise it is folded into 64-bit per-lane
         // addresses computed with vector instructions for every load
-        size_t toff = (size_t)tile * TILEB;
-        asm volatile("" : "+s"(toff));
-        const unsigned char* kp = kg + toff;
-        const unsigned char* vp = vg + toff;
+        // (contiguous tensors: K and V share every offset)
+        size_t koff = (size_t)tile * F8_BN * k_rs, voff = STRIDED ? (size_t)tile * F8_BN * v_rs : 0;
+        asm volatile("" : "+s"(koff));
+        if constexpr (STRIDED)
+            asm volatile("" : "+s"(voff));
+        const unsigned char* kp = kg + koff;
+        const unsigned char* vp = vg + (STRIDED ? voff : koff);
         if (tile == last_tile) {
 #pragma unroll
             for (int i = 0; i < LD_PER_T; ++i) {
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)g_off_last[i]);
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)g_off_last[i]);
+                // recomputed here rather than kept in registers for the whole kernel
+                const int L = tid + F8_THREADS * i;
+                const int row = L / CPR16, c16 = L % CPR16;
+                const int rl = row < rows_last ? row : rows_last - 1;
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)(rl * k_rs + c16 * 16));
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)(rl * v_rs + c16 * 16));
             }
         } else {
 #pragma unroll
             for (int i = 0; i < LD_PER_T; ++i) {
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)g_off[i]);
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)g_off[i]);
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)gk_off[i]);
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)(STRIDED ? gv_off[i] : gk_off[i]));
             }
         }
     };
@@ -332,7 +348,8 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     if (my_q < S) {
         if (p.lse != nullptr && h == 0)
             p.lse[(size_t)bh * S + my_q] = (m_run - F8_P_SHIFT + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
-        unsigned char* og = (unsigned char*)p.o + ((size_t)bh * S + my_q) * D * 2;
+        unsigned char* og = (unsigned char*)p.o +
+                            (STRIDED ? b * p.o_bs + hq * p.o_hs : (long long)bh * S * D * 2) + (size_t)my_q * o_rs;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -349,8 +366,9 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
 
 extern "C" {
 
-int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int S,
-                      int D, int causal, float scale, float descale_q, float descale_k, float descale_v, void* stream)
+int naut_attn_fwd_fp8_strided(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                              int S, int D, int causal, float scale, float descale_q, float descale_k,
+                              float descale_v, void* stream, const naut_strides* st)
 {
     if (!q || !k || !v || !o)
         return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
@@ -372,7 +390,38 @@ int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, floa
     if ((uintptr_t)lse & 3u)
         return fail(NAUT_ERR_ALIGN, "lse must be 4-byte aligned");
 
+    naut_strides cs;  // contiguous [B][H][S][D]
+    cs.q_s = cs.k_s = cs.v_s = cs.o_s = D;
+    cs.q_h = cs.o_h = cs.k_h = cs.v_h = (long long)S * D;
+    cs.q_b = cs.o_b = (long long)Hq * S * D;
+    cs.k_b = cs.v_b = (long long)Hkv * S * D;
+    if (!st)
+        st = &cs;
+    const long long in_strides[9] = {st->q_b, st->q_h, st->q_s, st->k_b, st->k_h, st->k_s, st->v_b, st->v_h, st->v_s};
+    for (long long x : in_strides)
+        if (x < 0 || x % 16 != 0)
+            return fail(NAUT_ERR_ALIGN, "q/k/v strides must be non-negative multiples of 16 elements (16 bytes)");
+    if (st->o_b <= 0 || st->o_h <= 0 || st->o_s <= 0 || st->o_b % 4 != 0 || st->o_h % 4 != 0 || st->o_s % 4 != 0)
+        return fail(NAUT_ERR_ALIGN, "o strides must be positive multiples of 4 elements");
+    if (st->q_s < D || st->k_s < D || st->v_s < D || st->o_s < D)
+        return fail(NAUT_ERR_SHAPE, "a sequence stride is smaller than D: rows would overlap");
+    const long long max_rs = 1LL << 23;  // elements: keeps 64 rows of byte offsets inside 32 bits
+    if (st->q_s > max_rs || st->k_s > max_rs || st->v_s > max_rs || st->o_s > max_rs)
+        return fail(NAUT_ERR_UNSUPPORTED, "sequence stride too large");
+
     Fp8Params p;
+    p.q_bs = st->q_b;
+    p.q_hs = st->q_h;
+    p.q_rs = (int)st->q_s;
+    p.k_bs = st->k_b;
+    p.k_hs = st->k_h;
+    p.k_rs = (int)st->k_s;
+    p.v_bs = st->v_b;
+    p.v_hs = st->v_h;
+    p.v_rs = (int)st->v_s;
+    p.o_bs = st->o_b * 2;
+    p.o_hs = st->o_h * 2;
+    p.o_rs = (int)(st->o_s * 2);
     p.q = q;
     p.k = k;
     p.v = v;
@@ -387,22 +436,34 @@ int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, floa
     p.c = c > 0.f ? c : 1e-30f;
     p.dv = descale_v;
     const dim3 grid((unsigned)nblocks);
-    hipStream_t st = (hipStream_t)stream;
-    if (D == 128) {
-        if (causal)
-            hipLaunchKernelGGL((naut_fwd_kernel_fp8<128, true>), grid, dim3(F8_THREADS), 0, st, p);
-        else
-            hipLaunchKernelGGL((naut_fwd_kernel_fp8<128, false>), grid, dim3(F8_THREADS), 0, st, p);
-    } else {
-        if (causal)
-            hipLaunchKernelGGL((naut_fwd_kernel_fp8<64, true>), grid, dim3(F8_THREADS), 0, st, p);
-        else
-            hipLaunchKernelGGL((naut_fwd_kernel_fp8<64, false>), grid, dim3(F8_THREADS), 0, st, p);
-    }
+    hipStream_t hs = (hipStream_t)stream;
+    // contiguous tensors (whoever says so) take the instantiation with compile-time strides
+    const bool strided = st->q_b != cs.q_b || st->q_h != cs.q_h || st->q_s != cs.q_s || st->k_b != cs.k_b ||
+                         st->k_h != cs.k_h || st->k_s != cs.k_s || st->v_b != cs.v_b || st->v_h != cs.v_h ||
+                         st->v_s != cs.v_s || st->o_b != cs.o_b || st->o_h != cs.o_h || st->o_s != cs.o_s;
+#define NAUT_F8_LAUNCH(DD, CC, SS)                                                          \
+    if (D == DD && (causal != 0) == CC && strided == SS)                                    \
+        hipLaunchKernelGGL((naut_fwd_kernel_fp8<DD, CC, SS>), grid, dim3(F8_THREADS), 0, hs, p);
+    NAUT_F8_LAUNCH(128, true, false)
+    NAUT_F8_LAUNCH(128, false, false)
+    NAUT_F8_LAUNCH(64, true, false)
+    NAUT_F8_LAUNCH(64, false, false)
+    NAUT_F8_LAUNCH(128, true, true)
+    NAUT_F8_LAUNCH(128, false, true)
+    NAUT_F8_LAUNCH(64, true, true)
+    NAUT_F8_LAUNCH(64, false, true)
+#undef NAUT_F8_LAUNCH
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_launch(e);
     return NAUT_OK;
+}
+
+int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int S,
+                      int D, int causal, float scale, float descale_q, float descale_k, float descale_v, void* stream)
+{
+    return naut_attn_fwd_fp8_strided(q, k, v, o, lse, B, Hq, Hkv, S, D, causal, scale, descale_q, descale_k, descale_v,
+                                     stream, nullptr);
 }
 
 }  // extern "C"

@@ -172,3 +172,17 @@ def test_fp8_argument_checks():
     assert f8(dq=0.0) == nb.NAUT_ERR_UNSUPPORTED
     assert f8(D=96) == nb.NAUT_ERR_UNSUPPORTED
     assert f8(q=A + 4) == nb.NAUT_ERR_ALIGN
+
+    def f8s(strides, **kw):
+        a = dict(q=A, B=1, Hq=2, Hkv=2, S=128, D=128)
+        a.update(kw)
+        return nb.naut_attn_fwd_fp8_strided_raw(a["q"], A, A, A, A, a["B"], a["Hq"], a["Hkv"], a["S"], a["D"], 1, 0.1,
+                                                1.0, 1.0, 1.0, None, strides)
+    H, S, D = 2, 128, 128
+    good = (S * H * D, D, H * D) * 4                                                  # sequence-major
+    assert f8s(good, q=None) == nb.NAUT_ERR_NULL
+    assert f8s(good, D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert f8s(good[:2] + (H * D + 8,) + good[3:]) == nb.NAUT_ERR_ALIGN              # q rows not 16-byte aligned
+    assert f8s(good[:5] + (D - 16,) + good[6:]) == nb.NAUT_ERR_SHAPE                 # k rows overlap
+    assert f8s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED          # v row stride too large
+    assert f8s(good[:11] + (0,)) == nb.NAUT_ERR_ALIGN                                # o rows would coincide
