@@ -177,6 +177,8 @@ int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, fl
  * sequence-major K/V cache [B][Sk][Hkv][D] has {Sk*Hkv*D, D, Hkv*D}.  Same rules as naut_attn_fwd_strided
  * (q/k/v strides non-negative multiples of 8, o strides positive multiples of 4, sequence strides between D
  * and 2^23); st = NULL means contiguous, which is what naut_attn_decode_dt passes.  lse stays dense.
+ * D may be any multiple of 8 up to 128 here (a narrower head runs on the 64- or 128-wide kernel, as in
+ * naut_attn_fwd_strided); naut_attn_decode and naut_attn_decode_dt keep D = 64 or 128.
  */
 int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* o, float* lse,
                              int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,

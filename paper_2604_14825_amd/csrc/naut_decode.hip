@@ -59,6 +59,10 @@ struct DecodeParams {
     // byte strides of batch, head and sequence position (the D axis is contiguous)
     long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
     int q_rs, k_rs, v_rs, o_rs;
+    // The kernels are compiled for D = 64 or 128; a smaller head dimension runs on the next wider one:
+    // cpr 16-byte chunks of every row are real, the chunks of Q beyond them read as zero, those of K and
+    // V repeat a real chunk (they meet zeros of Q, or end in columns of O that are not stored).
+    int cpr;
 };
 
 __device__ __forceinline__ float half_sum_f(float x)
@@ -107,7 +111,9 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     i32x4_t qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = *(const i32x4_t*)(qg + (row_ld / p.Sq) * p.q_hs + (long long)(row_ld % p.Sq) * p.q_rs + ks * 32 + h * 16);
+        qf[ks] = ks * 2 + h < p.cpr
+                     ? *(const i32x4_t*)(qg + (row_ld / p.Sq) * p.q_hs + (long long)(row_ld % p.Sq) * p.q_rs + ks * 32 + h * 16)
+                     : i32x4_t{0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
         asm volatile("" : "+v"(qf[ks]));
@@ -123,16 +129,19 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
             const int line = P >> 4, pos = P & 15;
             const int off = ((line << 4) + (pos ^ (line & 15))) * 16;  // byte offset in a dense [32][D] block
             k_row[n] = off / ROWB;
-            k_col[n] = off % ROWB;
+            const int kc = off % ROWB / 16;
+            k_col[n] = (kc < p.cpr ? kc : p.cpr - 1) * 16;
         }
         if constexpr (D == 128) {
             const int r = P >> 4, cc = P & 15;
+            const int vc = cc ^ ((r & 3) << 2);
             v_row[n] = r;
-            v_col[n] = (cc ^ ((r & 3) << 2)) * 16;
+            v_col[n] = (vc < p.cpr ? vc : p.cpr - 1) * 16;
         } else {
             const int r = P >> 3, cc = P & 7;
+            const int vc = cc ^ (((r >> 1) & 1) << 2);
             v_row[n] = r;
-            v_col[n] = (cc ^ (((r >> 1) & 1) << 2)) * 16;
+            v_col[n] = (vc < p.cpr ? vc : p.cpr - 1) * 16;
         }
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem + (unsigned)(wave * 4 * BLKB);
@@ -374,6 +383,8 @@ __global__ __launch_bounds__(MRG_THREADS) void naut_decode_merge_kernel(const De
     const int b = bhk / p.Hkv, hk = bhk % p.Hkv;
     const int head = hk * (p.Hq / p.Hkv) + r / p.Sq, pos = r % p.Sq;
     unsigned char* orow = (unsigned char*)p.o + b * p.o_bs + head * p.o_hs + (long long)pos * p.o_rs;
+    if (lane * EPT >= p.cpr * 8)
+        return;  // padding columns of a narrower head dimension
     if constexpr (DT_OUT == NAUT_F32) {
         float* og = (float*)orow + lane * EPT;
 #pragma unroll
@@ -438,8 +449,8 @@ extern "C" {
 size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D)
 {
     Plan pl;
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || Hq % Hkv != 0 || (D != 64 && D != 128) ||
-        !make_plan(B, Hq, Hkv, Sq, Sk, D, &pl))
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || Hq % Hkv != 0 || D <= 0 || D % 8 != 0 || D > 128 ||
+        !make_plan(B, Hq, Hkv, Sq, Sk, D <= 64 ? 64 : 128, &pl))
         return 0;
     return pl.ws_bytes;
 }
@@ -460,12 +471,13 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
         return fail(NAUT_ERR_SHAPE, "scale must be finite");
     if (scale < 0.f)
         return fail(NAUT_ERR_UNSUPPORTED, "negative scale is not supported");
-    if (D != 64 && D != 128)
-        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    if (D % 8 != 0 || D > 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 8, at most 128");
+    const int DK = D <= 64 ? 64 : 128;  // width the kernels are compiled for
     if ((in_dtype != NAUT_BF16 && in_dtype != NAUT_F16) || (out_dtype != in_dtype && out_dtype != NAUT_F32))
         return fail(NAUT_ERR_UNSUPPORTED, "supported dtypes: q/k/v bf16 or f16; o of the same type or f32");
     Plan pl;
-    if (!make_plan(B, Hq, Hkv, Sq, Sk, D, &pl))
+    if (!make_plan(B, Hq, Hkv, Sq, Sk, DK, &pl))
         return fail(NAUT_ERR_UNSUPPORTED, "shape exceeds the grid limits");
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)workspace) & 15)
         return fail(NAUT_ERR_ALIGN, "q, k, v, o and workspace must be 16-byte aligned");
@@ -526,9 +538,10 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
     p.o_bs = st->o_b * out_b;
     p.o_hs = st->o_h * out_b;
     p.o_rs = (int)(st->o_s * out_b);
+    p.cpr = D / 8;
     hipStream_t hs = (hipStream_t)stream;
 #define NAUT_DEC(DD, IN, OUT)                                  \
-    if (D == DD && in_dtype == IN && out_dtype == OUT)         \
+    if (DK == DD && in_dtype == IN && out_dtype == OUT)        \
         return launch_decode<DD, IN, OUT>(p, hs);
     NAUT_DEC(128, NAUT_BF16, NAUT_BF16)
     NAUT_DEC(128, NAUT_BF16, NAUT_F32)
@@ -546,6 +559,8 @@ int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, fl
                         int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
                         void* stream, int in_dtype, int out_dtype)
 {
+    if (D > 0 && D != 64 && D != 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128 (naut_attn_decode_strided takes other head dimensions)");
     return naut_attn_decode_strided(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale, workspace, workspace_bytes,
                                     stream, in_dtype, out_dtype, nullptr);
 }

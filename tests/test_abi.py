@@ -101,7 +101,9 @@ def test_decode_argument_checks():
     ws = nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 128)
     assert ws > 0 and ws % 16 == 0
     assert nb.decode_workspace_bytes(1, 8, 3, 1, 4096, 128) == 0   # Hq % Hkv
-    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 96) == 0    # D
+    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 96) == ws   # a narrower head runs on the 128-wide kernel
+    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 100) == 0   # D not a multiple of 8
+    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 136) == 0   # D too wide
     ok = dict(B=1, Hq=8, Hkv=2, Sq=1, Sk=4096, D=128, causal=1, scale=0.1)
 
     def dec(q=A, k=A, v=A, o=A, lse=A, wsp=A, wsb=ws, **kw):
@@ -136,7 +138,8 @@ def test_decode_argument_checks():
     assert dec_s(good[:5] + (D - 8,) + good[6:]) == nb.NAUT_ERR_SHAPE                # k rows overlap
     assert dec_s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED        # v row stride too large
     assert dec_s(good[:9] + (0,) + good[10:]) == nb.NAUT_ERR_ALIGN                   # o batch stride must be positive
-    assert dec_s(good, D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert dec_s(good, D=100) == nb.NAUT_ERR_UNSUPPORTED
+    assert dec_s(good, D=136) == nb.NAUT_ERR_UNSUPPORTED
 
 
 def test_strided_argument_checks():

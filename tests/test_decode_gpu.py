@@ -155,3 +155,26 @@ def test_decode_shared_cache_and_padded_rows():
     torch.cuda.synchronize()
     o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, True, scale)
     gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode shared cache")
+
+
+@pytest.mark.parametrize("D,B,Hq,Hkv,Sq,Sk,causal,idt,odt", [
+    (8, 1, 4, 2, 1, 300, True, synth.BF16, synth.F32),
+    (40, 2, 8, 2, 3, 777, True, synth.BF16, synth.BF16),
+    (80, 1, 16, 2, 5, 500, False, synth.F16, synth.F16),
+    (96, 2, 4, 4, 1, 2049, True, synth.BF16, synth.BF16),
+    (112, 1, 8, 1, 2, 1000, True, synth.F16, synth.F32),
+])
+def test_decode_other_head_dimensions(D, B, Hq, Hkv, Sq, Sk, causal, idt, odt):
+    """Multiples of 8 below 128 run on the 64- or 128-wide decode kernels (strided entry point, contiguous tensors)."""
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, idt, 7700 + Sk + D, Sk // 50)
+    scale = 1.0 / math.sqrt(D)
+    qd, kd, vd = (gu.to_device(a, idt) for a in (q, k, v))
+    od = torch.full((B, Hq, Sq, D), float("nan"), dtype=gu.TORCH_DT[odt], device="cuda")
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    print("decode head dim", D, flush=True)
+    nb.naut_attn_decode_strided(qd, kd, vd, od, lse, causal, scale, ws)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, causal, scale)
+    gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode D=%d" % D)
