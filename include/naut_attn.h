@@ -185,6 +185,17 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
                              void* workspace, size_t workspace_bytes, void* stream, int in_dtype, int out_dtype,
                              const naut_strides* st);
 
+/*
+ * Decode-time attention on an FP8 (E4M3) K/V cache, the setting in which the cache is the traffic that
+ * matters: q, k, v are E4M3 bytes with one scale per tensor as in naut_attn_fwd_fp8, contiguous
+ * [B][H][S][D]; o is bf16, lse fp32.  D is 64 or 128.  Workspace, masks and everything else as
+ * naut_attn_decode; a workspace of naut_attn_decode_workspace_bytes(...) of the same sizes is large enough.
+ */
+int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, float* lse,
+                         int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
+                         float descale_q, float descale_k, float descale_v,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace naut_attn_decode[_dt|_strided] needs for these sizes; 0 if they are unsupported.  Host only. */
 size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D);
 

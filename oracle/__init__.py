@@ -211,3 +211,11 @@ def attn_rows_e4m3(q_bits, k_bits, v_bits, dq: float, dk: float, dv: float, caus
     if rows is None:
         return o.reshape(B, Hq, S, D), lse.reshape(B, Hq, S)
     return o, lse
+
+
+def attn_cross_e4m3(q_bits, k_bits, v_bits, dq: float, dk: float, dv: float, causal: bool, scale: float):
+    """Decode-time attention on FP8 E4M3 bytes with per-tensor scales: q [B,Hq,Sq,D] (the last Sq positions),
+    k,v [B,Hkv,Sk,D] -> (o, lse).  The exact decoder followed by the fp64 cross-attention entry point (both
+    pinned on their own); at Sq = Sk it must agree with attn_rows_e4m3, which is a separate C path."""
+    return attn_cross_f64(float(dq) * decode_e4m3(q_bits), float(dk) * decode_e4m3(k_bits),
+                          float(dv) * decode_e4m3(v_bits), causal, scale)

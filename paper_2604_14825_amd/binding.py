@@ -25,7 +25,7 @@ NAUT_F32 = 2
 
 EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
            "naut_attn_variant_name", "naut_attn_decode", "naut_attn_decode_dt", "naut_attn_decode_workspace_bytes",
-           "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided", "naut_attn_fwd_fp8_strided")
+           "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided", "naut_attn_fwd_fp8_strided", "naut_attn_decode_fp8")
 
 
 class NautStrides(ctypes.Structure):
@@ -77,6 +77,8 @@ def lib():
         L.naut_attn_fwd_fp8_strided.restype = ci
         L.naut_attn_fwd_fp8_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp,
                                                 ctypes.POINTER(NautStrides)]
+        L.naut_attn_decode_fp8.restype = ci
+        L.naut_attn_decode_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp, sz, vp]
         L.naut_attn_decode_strided.restype = ci
         L.naut_attn_decode_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci,
                                                ctypes.POINTER(NautStrides)]
@@ -347,5 +349,40 @@ def naut_attn_fwd_fp8_strided(q, k, v, o, lse, causal: bool, scale: float, desca
     st = NautStrides(*[t.stride(a) for t in (q, k, v, o) for a in (0, 1, 2)])
     rc = naut_attn_fwd_fp8_strided_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, S, D,
                                        causal, scale, descale_q, descale_k, descale_v, stream.cuda_stream, st)
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())
+
+
+def naut_attn_decode_fp8_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale, dq, dk, dv,
+                             ws_ptr, ws_bytes, stream_ptr) -> int:
+    """Direct call with integer device addresses; returns the status code."""
+    return int(lib().naut_attn_decode_fp8(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, int(causal),
+                                          float(scale), float(dq), float(dk), float(dv), ws_ptr, ws_bytes, stream_ptr))
+
+
+def naut_attn_decode_fp8(q, k, v, o, lse, causal: bool, scale: float, descale_q: float, descale_k: float,
+                         descale_v: float, workspace, stream=None):
+    """Decode-time attention on FP8 E4M3 tensors: q [B,Hq,Sq,D], k,v [B,Hkv,Sk,D] 1-byte, contiguous; o bf16
+    [B,Hq,Sq,D]; lse fp32 [B,Hq,Sq] or None; workspace as for naut_attn_decode."""
+    import torch
+    for t in (q, k, v, o, workspace):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("q, k, v, o and workspace must be contiguous device tensors")
+    if any(t.element_size() != 1 for t in (q, k, v)) or o.dtype != torch.bfloat16:
+        raise ValueError("q, k, v must be 1-byte tensors (E4M3) and o bf16")
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    if tuple(k.shape) != (B, Hkv, Sk, D) or tuple(v.shape) != (B, Hkv, Sk, D) or tuple(o.shape) != (B, Hq, Sq, D):
+        raise ValueError("shape mismatch between q, k, v, o")
+    lse_ptr = None
+    if lse is not None:
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, Hq, Sq)):
+            raise ValueError("lse must be a contiguous fp32 device tensor [B,Hq,Sq]")
+        lse_ptr = lse.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    rc = naut_attn_decode_fp8_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, Sq, Sk, D,
+                                  causal, scale, descale_q, descale_k, descale_v, workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), stream.cuda_stream)
     if rc != NAUT_OK:
         raise NautError(rc, last_error_string())

@@ -55,7 +55,8 @@ struct DecodeParams {
     int nsplit;    // splits of the key axis
     int bps;       // 32-key blocks per split (a multiple of 4)
     int causal;
-    float c;       // scale * log2(e), > 0
+    float c;       // scale * log2(e) (FP8: times descale_q * descale_k), > 0
+    float dv;      // factor on O: 1 (16-bit inputs) or descale_v (FP8)
     // byte strides of batch, head and sequence position (the D axis is contiguous)
     long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
     int q_rs, k_rs, v_rs, o_rs;
@@ -72,6 +73,86 @@ __device__ __forceinline__ float half_sum_f(float x)
     return a + b;
 }
 
+// Tail of a split kernel: the four wavefronts' partial (O, m, l) are merged through LDS (each wavefront
+// reuses its own, now idle, region of REGION bytes) and the work-group's partial goes to the workspace.
+// m is the reference maximum the wavefront's l and O are relative to (log2 units).
+template <int D, int REGION>
+__device__ __forceinline__ void merge_wavefronts(unsigned char* smem, const f32x16_t (&oacc)[D / 32], float m_run,
+                                                 float l_run, const DecodeParams& p, int bhk, int chunk, int split)
+{
+    constexpr int DB = D / 32;
+    constexpr int OSTRIDE = D + 4;  // floats per row of the partial O in LDS (padded against bank conflicts)
+    static_assert(DEC_ROWS * OSTRIDE * 4 + 2 * DEC_ROWS * 4 <= REGION, "the wavefront's partial fits its LDS region");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+    unsigned char* my_lds = smem + wave * REGION;
+    // ---- merge the four wavefronts through LDS (each reuses its own, now idle, region) ----
+    float* my_o = (float*)my_lds;                          // [32][OSTRIDE]
+    float* my_ml = my_o + DEC_ROWS * OSTRIDE;              // m[32], l[32]
+    const float l_tot = half_sum_f(l_run);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const int d = 32 * db + 8 * gq + 4 * h;
+            const f32x4_t w = {oacc[db][4 * gq + 0], oacc[db][4 * gq + 1], oacc[db][4 * gq + 2], oacc[db][4 * gq + 3]};
+            *(f32x4_t*)(my_o + l32 * OSTRIDE + d) = w;
+        }
+    if (h == 0) {
+        my_ml[l32] = m_run;
+        my_ml[DEC_ROWS + l32] = l_tot;
+    }
+    __syncthreads();
+
+    // thread -> (row, D/8 consecutive d); partial written to the workspace
+    if (tid >= DEC_ROWS * 8)
+        return;
+    constexpr int DPT = D / 8;  // floats per thread: 16 (D = 128) or 8 (D = 64)
+    const int r_out = tid >> 3, d0 = (tid & 7) * DPT;
+    float mw[DEC_WAVES], lw[DEC_WAVES];
+    float M = DEC_M_INIT;
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) {
+        const float* ml = (const float*)(smem + w * REGION) + DEC_ROWS * OSTRIDE;
+        mw[w] = ml[r_out];
+        lw[w] = ml[DEC_ROWS + r_out];
+        M = fmaxf(M, mw[w]);
+    }
+    float L = 0.f;
+    f32x4_t acc[DPT / 4];
+#pragma unroll
+    for (int i = 0; i < DPT / 4; ++i)
+        acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) {
+        const float f = __builtin_amdgcn_exp2f(mw[w] - M);
+        L += f * lw[w];
+        const float* ow = (const float*)(smem + w * REGION) + r_out * OSTRIDE + d0;
+#pragma unroll
+        for (int i = 0; i < DPT / 4; ++i) {
+            const f32x4_t x = *(const f32x4_t*)(ow + 4 * i);
+            acc[i] += x * f;
+        }
+    }
+    const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
+    const size_t part = ((size_t)bhk * p.nchunks + chunk) * p.nsplit + split;
+    if (chunk * DEC_ROWS + r_out >= p.R)
+        return;  // rows past the last one are padding: nobody reads their partials
+    float* ws_o = p.ws + (part * DEC_ROWS + r_out) * D + d0;
+#pragma unroll
+    for (int i = 0; i < DPT / 4; ++i)
+        *(f32x4_t*)(ws_o + 4 * i) = acc[i];
+    if ((tid & 7) == 0) {
+        float* ws_m = p.ws + nparts * DEC_ROWS * D;
+        float* ws_l = ws_m + nparts * DEC_ROWS;
+        ws_m[part * DEC_ROWS + r_out] = M;
+        ws_l[part * DEC_ROWS + r_out] = L;
+    }
+}
+
 template <int D, int DT_IN>
 __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const DecodeParams p)
 {
@@ -81,8 +162,6 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
     constexpr int NLD = BLKB / 1024;       // direct loads (1 KB each) per block and operand
-    constexpr int OSTRIDE = D + 4;         // floats per row of the partial O in LDS (padded against bank conflicts)
-    static_assert(DEC_ROWS * OSTRIDE * 4 + 2 * DEC_ROWS * 4 <= 4 * BLKB, "the wavefront's partial fits its LDS region");
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[DEC_WAVES * 4 * BLKB];  // per wavefront: K0 V0 K1 V1
 
@@ -254,68 +333,213 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
         }
     }
 
-    // ---- merge the four wavefronts through LDS (each reuses its own, now idle, region) ----
-    float* my_o = (float*)my_lds;                          // [32][OSTRIDE]
-    float* my_ml = my_o + DEC_ROWS * OSTRIDE;              // m[32], l[32]
-    const float l_tot = half_sum_f(l_run);
+    merge_wavefronts<D, 4 * BLKB>(smem, oacc, m_run, l_run, p, bhk, chunk, split);
+}
+
+// The same split kernel on FP8 (E4M3) Q, K and V, contiguous tensors: 64-key blocks (one 32x32x64 MFMA
+// covers 64 keys of P.V), the LDS layouts, transposed byte reads and the 2^7 scaling of P of the FP8
+// prefill kernel, the blocks dealt to the wavefronts and double-buffered in LDS exactly as above.
+// bps counts 64-key blocks here.  The partial's reference maximum is stored as m - 7, which makes its l
+// and O (both carry the factor 2^7) relative to it in the plain sense the merge kernel expects.
+constexpr int DEC8_BLK = 64;
+constexpr float DEC8_TAU = 1.0f;      // P * 2^7 <= 2^(1+7) = 256 < 448, the largest E4M3 value
+constexpr float DEC8_P_SHIFT = 7.0f;
+
+template <int D>
+__global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(const DecodeParams p)
+{
+    constexpr int BLKB = DEC8_BLK * D;     // bytes of one 64-key block of K or V
+    constexpr int KS = D / 64;
+    constexpr int DB = D / 32;
+    constexpr int CPR = D / 16;            // 16-byte chunks per row
+    constexpr int NLD = BLKB / 1024;       // direct loads (1 KB each) per block and operand
+
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[DEC_WAVES * 4 * BLKB];  // per wavefront: K0 V0 K1 V1
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+
+    const int split = blockIdx.x, chunk = blockIdx.y, bhk = blockIdx.z;
+    const int b = bhk / p.Hkv, hk = bhk % p.Hkv;
+    const int g = p.Hq / p.Hkv;
+    const int Sk = p.Sk;
+    const float c = p.c;
+
+    // contiguous tensors: the R rows of this (batch, K/V head) follow each other in q
+    const unsigned char* qg = (const unsigned char*)p.q + (size_t)(b * p.Hq + hk * g) * p.Sq * D;
+    const unsigned char* kg = (const unsigned char*)p.k + (size_t)bhk * Sk * D;
+    const unsigned char* vg = (const unsigned char*)p.v + (size_t)bhk * Sk * D;
+
+    const int row = chunk * DEC_ROWS + l32;                 // the query row this lane owns
+    const int row_ld = row < p.R ? row : p.R - 1;
+    const int lim = p.causal ? Sk - p.Sq + (row_ld % p.Sq) : Sk - 1;  // last key this row may see
+
+    // Q^T fragments (MFMA B operand): lane holds q[row][64*ks + 32*h .. +32]
+    i32x8_t qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const i32x4_t lo = *(const i32x4_t*)(qg + (size_t)row_ld * D + ks * 64 + h * 32);
+        const i32x4_t hi = *(const i32x4_t*)(qg + (size_t)row_ld * D + ks * 64 + h * 32 + 16);
+        qf[ks] = i32x8_t{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        asm volatile("" : "+v"(qf[ks]));
+
+    // Direct global->LDS loads: instruction n fills physical 16-byte chunks 64n..64n+63 of the block, lane i
+    // the chunk 64n+i, so the lane fetches the logical chunk that k8_off / v8_off place there.
+    int k_row[NLD], k_col[NLD], v_row[NLD], v_col[NLD];
+#pragma unroll
+    for (int n = 0; n < NLD; ++n) {
+        const int P = n * 64 + lane;
+        const int r = P / CPR, pc = P % CPR;
+        k_row[n] = r;
+        k_col[n] = (pc ^ ((r >> 1) & (CPR - 1))) * 16;
+        const int key = D == 128 ? (((r >> 1) & 1) | (((r >> 3) & 1) << 1)) : ((r >> 3) & 1);
+        v_row[n] = r;
+        v_col[n] = (((pc >> 1) ^ key) << 5) + (pc & 1) * 16;
+    }
+    const unsigned lds0 = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem + (unsigned)(wave * 4 * BLKB);
+    unsigned char* my_lds = smem + wave * 4 * BLKB;
+
+    const int nblk = (Sk + DEC8_BLK - 1) / DEC8_BLK;
+    const int blk_begin = split * p.bps;
+    const int blk_end = blk_begin + p.bps < nblk ? blk_begin + p.bps : nblk;
+
+    auto issue = [&](int blk, int buf) {
+        const unsigned char* kp = kg + (size_t)blk * BLKB;
+        const unsigned char* vp = vg + (size_t)blk * BLKB;
+        const int rows_left = Sk - blk * DEC8_BLK;  // >= 1
+        const unsigned dst = lds0 + (unsigned)(buf * 2 * BLKB);
+#pragma unroll
+        for (int n = 0; n < NLD; ++n) {
+            int kr = k_row[n], vr = v_row[n];
+            if (rows_left < DEC8_BLK) {  // ragged last block: re-read the last row instead of running past the end
+                kr = kr < rows_left ? kr : rows_left - 1;
+                vr = vr < rows_left ? vr : rows_left - 1;
+            }
+            const int ko = kr * D + k_col[n], vo = vr * D + v_col[n];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst + n * 1024), "v"(ko), "s"(kp)
+                         : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst + BLKB + n * 1024), "v"(vo), "s"(vp)
+                         : "memory", "m0");
+        }
+    };
+
+    // lane-constant parts of the transposed V reads (as in the FP8 prefill kernel)
+    const int i16 = lane & 15;
+    const int v_e = i16 >> 1;
+    const int v_key = 4 * h + (v_e & 3) + ((v_e >> 2) << 3);
+    const int v_byte = 16 * ((lane >> 4) & 1) + 8 * (i16 & 1);
+
+    f32x16_t oacc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const int d = 32 * db + 8 * gq + 4 * h;
-            const f32x4_t w = {oacc[db][4 * gq + 0], oacc[db][4 * gq + 1], oacc[db][4 * gq + 2], oacc[db][4 * gq + 3]};
-            *(f32x4_t*)(my_o + l32 * OSTRIDE + d) = w;
-        }
-    if (h == 0) {
-        my_ml[l32] = m_run;
-        my_ml[DEC_ROWS + l32] = l_tot;
-    }
-    __syncthreads();
+        for (int r = 0; r < 16; ++r)
+            oacc[db][r] = 0.f;
+    float m_run = DEC_M_INIT;
+    float l_run = 0.f;
+    i32x8_t pb = {0, 0, 0, 0, 0, 0, 0, 0};
 
-    // thread -> (row, D/8 consecutive d); partial written to the workspace
-    if (tid >= DEC_ROWS * 8)
-        return;
-    constexpr int DPT = D / 8;  // floats per thread: 16 (D = 128) or 8 (D = 64)
-    const int r_out = tid >> 3, d0 = (tid & 7) * DPT;
-    float mw[DEC_WAVES], lw[DEC_WAVES];
-    float M = DEC_M_INIT;
+    static_assert(2 * NLD < 64, "vmcnt field");
+    int blk = blk_begin + wave;
+    if (blk < blk_end)
+        issue(blk, 0);
+    for (int it = 0; blk < blk_end; blk += DEC_WAVES, ++it) {
+        const int buf = it & 1;
+        const bool more = blk + DEC_WAVES < blk_end;
+        if (more) {
+            issue(blk + DEC_WAVES, buf ^ 1);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NLD) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        const unsigned char* kt = my_lds + buf * 2 * BLKB;
+        const unsigned char* vt = kt + BLKB;
+
+        f32x16_t sacc[2];
 #pragma unroll
-    for (int w = 0; w < DEC_WAVES; ++w) {
-        const float* ml = (const float*)(smem + w * 4 * BLKB) + DEC_ROWS * OSTRIDE;
-        mw[w] = ml[r_out];
-        lw[w] = ml[DEC_ROWS + r_out];
-        M = fmaxf(M, mw[w]);
-    }
-    float L = 0.f;
-    f32x4_t acc[DPT / 4];
+        for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-    for (int i = 0; i < DPT / 4; ++i)
-        acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            for (int r = 0; r < 16; ++r)
+                sacc[kb][r] = 0.f;
 #pragma unroll
-    for (int w = 0; w < DEC_WAVES; ++w) {
-        const float f = __builtin_amdgcn_exp2f(mw[w] - M);
-        L += f * lw[w];
-        const float* ow = (const float*)(smem + w * 4 * BLKB) + r_out * OSTRIDE + d0;
+            for (int ks = 0; ks < KS; ++ks) {
+                const int rw = kb * 32 + l32, c0 = ks * 4 + h * 2;
+                const i32x4_t lo = *(const i32x4_t*)(kt + k8_off<D>(rw, c0));
+                const i32x4_t hi = *(const i32x4_t*)(kt + k8_off<D>(rw, c0 + 1));
+                const i32x8_t kf = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                sacc[kb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[ks], sacc[kb], 0, 0, 0, 0, 0, 0);
+            }
+        }
+        const int key0 = blk * DEC8_BLK;
+        if (key0 + DEC8_BLK - 1 > Sk - p.Sq || key0 + DEC8_BLK > Sk) {  // some row's limit may fall inside the block
 #pragma unroll
-        for (int i = 0; i < DPT / 4; ++i) {
-            const f32x4_t x = *(const f32x4_t*)(ow + 4 * i);
-            acc[i] += x * f;
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    sacc[kb][r] = key > lim ? -INFINITY : sacc[kb][r];
+                }
+        }
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                mx = fmaxf(mx, sacc[kb][r]);
+        mx = half_max(mx);
+        const float m_cand = mx * c;  // -inf if the whole block is masked for this row
+        if (__builtin_amdgcn_ballot_w64(m_cand > m_run + DEC8_TAU) != 0) {
+            const float m_new = fmaxf(m_run, m_cand);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // repair factor
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    oacc[db][r] *= alpha;
+        }
+        const float shift = DEC8_P_SHIFT - m_run;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, shift));
+                sacc[kb][r] = pv;
+                psum += pv;
+            }
+        l_run += psum;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            const int kb = w >> 2, r0 = (w & 3) * 4;
+            pb[w] = pack4_fp8(sacc[kb][r0 + 0], sacc[kb][r0 + 1], sacc[kb][r0 + 2], sacc[kb][r0 + 3], pb[w]);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            i32x8_t vf;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int key = 32 * (t >> 1) + 16 * (t & 1) + v_key;
+                const i32x2_t x = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                    (NAUT_LDS i32x2_t*)(vt + v8_off<D>(key, db) + v_byte));
+                vf[2 * t] = x.x;
+                vf[2 * t + 1] = x.y;
+            }
+            oacc[db] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pb, oacc[db], 0, 0, 0, 0, 0, 0);
         }
     }
-    const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
-    const size_t part = ((size_t)bhk * p.nchunks + chunk) * p.nsplit + split;
-    if (chunk * DEC_ROWS + r_out >= p.R)
-        return;  // rows past the last one are padding: nobody reads their partials
-    float* ws_o = p.ws + (part * DEC_ROWS + r_out) * D + d0;
-#pragma unroll
-    for (int i = 0; i < DPT / 4; ++i)
-        *(f32x4_t*)(ws_o + 4 * i) = acc[i];
-    if ((tid & 7) == 0) {
-        float* ws_m = p.ws + nparts * DEC_ROWS * D;
-        float* ws_l = ws_m + nparts * DEC_ROWS;
-        ws_m[part * DEC_ROWS + r_out] = M;
-        ws_l[part * DEC_ROWS + r_out] = L;
-    }
+    merge_wavefronts<D, 4 * BLKB>(smem, oacc, m_run - DEC8_P_SHIFT, l_run, p, bhk, chunk, split);
 }
 
 // One work-group (four wavefronts) per query row: merges the nsplit partials of the row, divides by l
@@ -376,7 +600,7 @@ __global__ __launch_bounds__(MRG_THREADS) void naut_decode_merge_kernel(const De
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
         acc[e] = red_o[0][lane * EPT + e] + red_o[1][lane * EPT + e] + red_o[2][lane * EPT + e] + red_o[3][lane * EPT + e];
-    const float inv_l = 1.0f / L;
+    const float inv_l = p.dv / L;
     // lse is dense [B][Hq][Sq]: the R rows of (batch, K/V head) bhk are contiguous there
     if (p.lse != nullptr && lane == 0)
         p.lse[(size_t)bhk * p.R + r] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
@@ -526,6 +750,7 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
     p.causal = causal ? 1 : 0;
     const float cc = scale * 1.4426950408889634f;
     p.c = cc > 0.f ? cc : 1.0e-30f;  // scale == 0: every score becomes (almost exactly) 0, the softmax uniform
+    p.dv = 1.0f;
     p.q_bs = st->q_b * 2;
     p.q_hs = st->q_h * 2;
     p.q_rs = (int)(st->q_s * 2);
@@ -553,6 +778,84 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
     NAUT_DEC(64, NAUT_F16, NAUT_F32)
 #undef NAUT_DEC
     return fail(NAUT_ERR_UNSUPPORTED, "no kernel for this (D, dtype) combination");
+}
+
+int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                         int Sq, int Sk, int D, int causal, float scale, float descale_q, float descale_k,
+                         float descale_v, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o)
+        return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || D <= 0)
+        return fail(NAUT_ERR_SHAPE, "B, Hq, Hkv, Sq, Sk and D must be positive");
+    if (Hq % Hkv != 0)
+        return fail(NAUT_ERR_SHAPE, "Hq must be a multiple of Hkv");
+    if (causal && Sk < Sq)
+        return fail(NAUT_ERR_SHAPE, "with the causal mask the Sq queries are the last positions of Sk: Sk >= Sq");
+    if (!std::isfinite(scale) || !std::isfinite(descale_q) || !std::isfinite(descale_k) || !std::isfinite(descale_v))
+        return fail(NAUT_ERR_SHAPE, "scale and the three descale factors must be finite");
+    if (scale < 0.f || descale_q <= 0.f || descale_k <= 0.f || descale_v <= 0.f)
+        return fail(NAUT_ERR_UNSUPPORTED, "scale must be >= 0 and the descale factors > 0");
+    if (D != 64 && D != 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    Plan pl;  // over 64-key blocks: the plan of a cache half as long in 32-key blocks
+    if (!make_plan(B, Hq, Hkv, Sq, (Sk + 1) / 2, D, &pl))
+        return fail(NAUT_ERR_UNSUPPORTED, "shape exceeds the grid limits");
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)workspace) & 15)
+        return fail(NAUT_ERR_ALIGN, "q, k, v, o and workspace must be 16-byte aligned");
+    if ((uintptr_t)lse & 3)
+        return fail(NAUT_ERR_ALIGN, "lse must be 4-byte aligned");
+    if (!workspace || workspace_bytes < pl.ws_bytes)
+        return fail(NAUT_ERR_SHAPE, "workspace is NULL or smaller than naut_attn_decode_workspace_bytes()");
+
+    DecodeParams p;
+    p.q = q;
+    p.k = k;
+    p.v = v;
+    p.o = o;
+    p.lse = lse;
+    p.ws = (float*)workspace;
+    p.B = B;
+    p.Hq = Hq;
+    p.Hkv = Hkv;
+    p.Sq = Sq;
+    p.Sk = Sk;
+    p.R = Hq / Hkv * Sq;
+    p.nchunks = pl.nchunks;
+    p.nsplit = pl.nsplit;
+    p.bps = pl.bps;
+    p.causal = causal ? 1 : 0;
+    const float cc = scale * descale_q * descale_k * 1.4426950408889634f;
+    p.c = cc > 0.f ? cc : 1.0e-30f;
+    p.dv = descale_v;
+    // o: contiguous bf16 [B][Hq][Sq][D] (the merge kernel addresses it through strides); q, k, v: the split
+    // kernel indexes them as contiguous bytes itself
+    p.q_bs = p.q_hs = p.k_bs = p.k_hs = p.v_bs = p.v_hs = 0;
+    p.q_rs = p.k_rs = p.v_rs = 0;
+    p.o_bs = (long long)Hq * Sq * D * 2;
+    p.o_hs = (long long)Sq * D * 2;
+    p.o_rs = D * 2;
+    p.cpr = D / 8;
+    hipStream_t hs = (hipStream_t)stream;
+    const dim3 g1((unsigned)p.nsplit, (unsigned)p.nchunks, (unsigned)(p.B * p.Hkv));
+    const dim3 g2((unsigned)p.R, (unsigned)(p.B * p.Hkv));
+    if (D == 128) {
+        hipLaunchKernelGGL((naut_decode_split_fp8_kernel<128>), g1, dim3(DEC_THREADS), 0, hs, p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return fail_launch(e);
+        hipLaunchKernelGGL((naut_decode_merge_kernel<128, NAUT_BF16>), g2, dim3(MRG_THREADS), 0, hs, p);
+    } else {
+        hipLaunchKernelGGL((naut_decode_split_fp8_kernel<64>), g1, dim3(DEC_THREADS), 0, hs, p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return fail_launch(e);
+        hipLaunchKernelGGL((naut_decode_merge_kernel<64, NAUT_BF16>), g2, dim3(MRG_THREADS), 0, hs, p);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_launch(e);
+    return NAUT_OK;
 }
 
 int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,

@@ -36,8 +36,6 @@ namespace {
 
 using namespace naut;
 
-typedef int i32x8_t __attribute__((ext_vector_type(8)));
-
 constexpr int F8_BM = 128;
 constexpr int F8_BN = 64;
 constexpr int F8_WAVES = 4;
@@ -61,34 +59,6 @@ struct Fp8Params {
     long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
     int q_rs, k_rs, v_rs, o_rs;
 };
-
-// K tile: 64 rows of D bytes; the 16-byte chunks of a row are XOR-ed with (row/2), so that the 32 lanes
-// that read the same chunk of 32 consecutive rows cover all banks (measured: no bank conflicts).
-template <int D>
-__device__ __forceinline__ int k8_off(int row, int c16)
-{
-    constexpr int CPR = D / 16;
-    return row * D + ((c16 ^ ((row >> 1) & (CPR - 1))) << 4);
-}
-// V tile: rows of D bytes in 32-byte chunks.  One transposed read touches, per half of the wavefront, 8
-// rows (r0 + {0,1,2,3,8,9,10,11}) x 32 bytes = 256 bytes, one access per bank if the 8 rows land in 8
-// different bank groups: row parity gives two (128-byte rows) and the chunk position is XOR-ed with bits
-// 1 and 3 of the row number for the other four (D = 64: 64-byte rows, bits 0..1 give four, bit 3 the rest).
-template <int D>
-__device__ __forceinline__ int v8_off(int row, int c32)
-{
-    const int key = D == 128 ? (((row >> 1) & 1) | (((row >> 3) & 1) << 1)) : ((row >> 3) & 1);
-    return row * D + ((c32 ^ key) << 5);
-}
-
-// Four floats to four E4M3 bytes.  The conversion writes one 16-bit half of its destination and keeps the
-// other; `old` is whatever the register held (both halves get written, so it only saves the instruction
-// that would clear it).
-__device__ __forceinline__ int pack4_fp8(float x0, float x1, float x2, float x3, int old)
-{
-    const int w = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, old, false);
-    return __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, w, true);
-}
 
 // STRIDED = false: contiguous [B][H][S][D] tensors, every stride a compile-time constant (the launch
 // parameters' strides are not read); true: strides from the launch parameters.

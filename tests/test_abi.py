@@ -142,6 +142,22 @@ def test_decode_argument_checks():
     assert dec_s(good, D=136) == nb.NAUT_ERR_UNSUPPORTED
 
 
+def test_decode_fp8_argument_checks():
+    ws = nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 128)
+
+    def d8(q=A, k=A, wsp=A, wsb=ws, B=1, Hq=8, Hkv=2, Sq=1, Sk=4096, D=128, causal=1, scale=0.1, dq=1.0, dk=1.0, dv=1.0):
+        return nb.naut_attn_decode_fp8_raw(q, k, A, A, A, B, Hq, Hkv, Sq, Sk, D, causal, scale, dq, dk, dv, wsp, wsb, None)
+    assert d8(q=None) == nb.NAUT_ERR_NULL
+    assert d8(Sk=0) == nb.NAUT_ERR_SHAPE
+    assert d8(Sq=5000) == nb.NAUT_ERR_SHAPE
+    assert d8(dk=float("inf")) == nb.NAUT_ERR_SHAPE
+    assert d8(dv=0.0) == nb.NAUT_ERR_UNSUPPORTED
+    assert d8(D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert d8(k=A + 8) == nb.NAUT_ERR_ALIGN
+    assert d8(wsp=None) == nb.NAUT_ERR_SHAPE
+    assert d8(wsb=16) == nb.NAUT_ERR_SHAPE
+
+
 def test_strided_argument_checks():
     bf = nb.NAUT_BF16
     D = 96

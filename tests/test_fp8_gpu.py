@@ -116,3 +116,30 @@ def test_fp8_sequence_major_layout(B, Hq, Hkv, S, D, causal):
     o_ref, lse_ref = oracle.attn_rows_e4m3(q, k, v, DQ, DK, DV, causal, scale)
     check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, v, "fp8 bshd")
     assert torch.all(o_mem[..., D:] == 7.0).item(), "the gaps between O rows were written"
+
+
+DEC_CASES = [
+    # B, Hq, Hkv, Sq, Sk, D, causal
+    (1, 1, 1, 1, 1, 64, False), (1, 2, 2, 1, 63, 128, True), (1, 4, 4, 1, 100, 128, True),
+    (2, 8, 2, 1, 777, 128, True), (1, 8, 1, 3, 500, 64, True), (1, 16, 2, 5, 300, 128, True),
+    (1, 2, 2, 1, 4096, 128, False), (1, 2, 1, 64, 64, 64, True), (3, 6, 3, 2, 2049, 128, True),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", DEC_CASES)
+def test_fp8_decode_elementwise(B, Hq, Hkv, Sq, Sk, D, causal):
+    """Decode-time attention on an FP8 K/V cache against the fp64 oracle on the same bytes."""
+    q = synth.fill_e4m3(B, Hq, Sq, D, 11500 + Sk + D, synth.TAG_Q, DQ)
+    k = synth.fill_e4m3(B, Hkv, Sk, D, 11500 + Sk + D, synth.TAG_K, DK, Sk // 50, 8.0)
+    v = synth.fill_e4m3(B, Hkv, Sk, D, 11500 + Sk + D, synth.TAG_V, DV)
+    scale = 1.0 / math.sqrt(D)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    o = torch.full((B, Hq, Sq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    print("fp8 decode", B, Hq, Hkv, Sq, Sk, D, causal, flush=True)
+    nb.naut_attn_decode_fp8(dev(q), dev(k), dev(v), o, lse, causal, scale, DQ, DK, DV, ws)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_cross_e4m3(q, k, v, DQ, DK, DV, causal, scale)
+    check(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, v, "fp8 decode")

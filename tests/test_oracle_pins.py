@@ -457,3 +457,24 @@ def test_e4m3_rows_entry_matches_f64_entry(causal):
     o3, l3 = oracle.attn_rows_e4m3(q, k, v, dq, dk, dv, causal, 0.35, rows=rows)
     np.testing.assert_array_equal(o3, o2.reshape(-1, D)[rows])
     np.testing.assert_array_equal(l3, l2.reshape(-1)[rows])
+
+
+def test_e4m3_cross_entry_agrees_with_the_rows_entry_and_with_a_tail():
+    """attn_cross_e4m3 (decoder + fp64 cross entry) against attn_rows_e4m3 (its own C path) at Sq = Sk, and
+    against the last Sq rows of a causal self-attention over Sk (bottom-right alignment)."""
+    from paper_2604_14825_amd import synth
+    B, Hq, Hkv, S, D = 2, 4, 2, 37, 64
+    dq, dk, dv = 1 / 64, 1 / 8, 1 / 64
+    q = synth.fill_e4m3(B, Hq, S, D, 31, synth.TAG_Q, dq)
+    k = synth.fill_e4m3(B, Hkv, S, D, 31, synth.TAG_K, dk, 1, 8.0)
+    v = synth.fill_e4m3(B, Hkv, S, D, 31, synth.TAG_V, dv)
+    for causal in (False, True):
+        o1, l1 = oracle.attn_cross_e4m3(q, k, v, dq, dk, dv, causal, 0.2)
+        o2, l2 = oracle.attn_rows_e4m3(q, k, v, dq, dk, dv, causal, 0.2)
+        np.testing.assert_allclose(o1, o2, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(l1, l2, rtol=1e-12, atol=1e-14)
+    Sq = 5
+    o_t, l_t = oracle.attn_cross_e4m3(np.ascontiguousarray(q[:, :, S - Sq:]), k, v, dq, dk, dv, True, 0.2)
+    o_f, l_f = oracle.attn_rows_e4m3(q, k, v, dq, dk, dv, True, 0.2)
+    np.testing.assert_allclose(o_t, o_f[:, :, S - Sq:], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(l_t, l_f[:, :, S - Sq:], rtol=1e-12, atol=1e-14)
