@@ -35,6 +35,8 @@ MEASURED_TRAFFIC_BYTES = {
     "decode": 5.387e8,
     # profiles/naut_fwd_fp8_long_S16384_D128_causal.md: 564080 KiB x 2.000 read + 133170 KiB written
     "long_fp8": 1.292e9,
+    # profiles/naut_decode_fp8_B8_Hq32_Hkv8_Sk16384_D128.md: (131210 + 410) KiB x 2.000 read + (528 + 72) KiB written
+    "decode_fp8": 2.702e8,
     # profiles/naut_fwd_bm128_w4q32_bn32_long_S16384_D256_causal.md: 2604500 KiB x 2.000 read + 264190 KiB written
     "long_d256": 5.60e9,
 }
@@ -196,15 +198,23 @@ def bench_fp8(args, nb, synth, torch, np) -> int:
     return 0
 
 
-def bench_decode(args, nb, synth, torch, np) -> int:
-    """One step = one naut_attn_decode call (split kernel + merge kernel) over the resident cache."""
+def bench_decode(args, nb, synth, torch, np, fp8=False) -> int:
+    """One step = one naut_attn_decode (or naut_attn_decode_fp8) call (split kernel + merge kernel) over the
+    resident cache."""
     c = DECODE
     B, Hq, Hkv, Sq, Sk, D = c["B"], c["Hq"], c["Hkv"], c["Sq"], c["Sk"], c["D"]
     seed = synth.BASE_SEED + 100
-    q = synth.fill(B, Hq, Sq, D, seed, synth.TAG_Q, synth.BF16)
-    k = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_K, synth.BF16, int(c["outlier_frac"] * Sk), c["outlier_scale"])
-    v = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_V, synth.BF16)
-    dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    if fp8:
+        q = synth.fill_e4m3(B, Hq, Sq, D, seed, synth.TAG_Q, FP8_DESCALE["q"])
+        k = synth.fill_e4m3(B, Hkv, Sk, D, seed, synth.TAG_K, FP8_DESCALE["k"], int(c["outlier_frac"] * Sk),
+                            c["outlier_scale"])
+        v = synth.fill_e4m3(B, Hkv, Sk, D, seed, synth.TAG_V, FP8_DESCALE["v"])
+        dev = lambda a: torch.from_numpy(a).cuda()
+    else:
+        q = synth.fill(B, Hq, Sq, D, seed, synth.TAG_Q, synth.BF16)
+        k = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_K, synth.BF16, int(c["outlier_frac"] * Sk), c["outlier_scale"])
+        v = synth.fill(B, Hkv, Sk, D, seed, synth.TAG_V, synth.BF16)
+        dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
     qd, kd, vd = dev(q), dev(k), dev(v)
     o = torch.empty((B, Hq, Sq, D), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((B, Hq, Sq), dtype=torch.float32, device="cuda")
@@ -213,7 +223,11 @@ def bench_decode(args, nb, synth, torch, np) -> int:
     scale = D ** -0.5
 
     def step():
-        nb.naut_attn_decode(qd, kd, vd, o, lse, True, scale, ws, stream=stream)
+        if fp8:
+            nb.naut_attn_decode_fp8(qd, kd, vd, o, lse, True, scale, FP8_DESCALE["q"], FP8_DESCALE["k"],
+                                    FP8_DESCALE["v"], ws, stream=stream)
+        else:
+            nb.naut_attn_decode(qd, kd, vd, o, lse, True, scale, ws, stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -230,9 +244,10 @@ def bench_decode(args, nb, synth, torch, np) -> int:
     ms_wall = (t1 - t0) * 1e3 / args.steps
     ms_kernel = ev.elapsed_ms(e0, e1) / args.steps
     # algorithmic bytes: Q, K, V read once; O and LSE written once (the partials in the workspace are extra)
-    nbytes = (B * Hq * Sq * D + 2 * B * Hkv * Sk * D) * 2 + B * Hq * Sq * D * 2 + B * Hq * Sq * 4
+    in_b = 1 if fp8 else 2
+    nbytes = (B * Hq * Sq * D + 2 * B * Hkv * Sk * D) * in_b + B * Hq * Sq * D * 2 + B * Hq * Sq * 4
     out = {
-        "metric": "decode attention GB/s (B=8, 32/8 heads, Sk=16k, D=128)",
+        "metric": "decode attention GB/s (B=8, 32/8 heads, Sk=16k, D=128)" + (", FP8 E4M3 cache" if fp8 else ""),
         "value": nbytes / (ms_wall * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1,
@@ -242,14 +257,15 @@ def bench_decode(args, nb, synth, torch, np) -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "fp8_e4m3" if fp8 else "bf16",
         "data": "synthetic",
-        "config": {"workload": "decode", "B": B, "Hq": Hq, "Hkv": Hkv, "Sq": Sq, "Sk": Sk, "D": D, "causal": True,
-                   "outlier_k_rows": int(c["outlier_frac"] * Sk), "kernel": "decode_split32x32 + merge",
+        "config": {"workload": "decode_fp8" if fp8 else "decode", "B": B, "Hq": Hq, "Hkv": Hkv, "Sq": Sq, "Sk": Sk, "D": D, "causal": True,
+                   "outlier_k_rows": int(c["outlier_frac"] * Sk),
+                   "kernel": "decode_split_fp8_32x32x64 + merge" if fp8 else "decode_split32x32 + merge",
                    "workspace_bytes": int(ws.numel())},
         "roofline": {"bound": "hbm", "achieved": nbytes / (ms_kernel * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": nbytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get("decode"), "kernel_ms": ms_kernel,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get("decode_fp8" if fp8 else "decode"), "kernel_ms": ms_kernel,
                      "algorithmic_hbm_bytes": nbytes},
         "context": PAPER_CONTEXT,
     }
@@ -258,7 +274,11 @@ def bench_decode(args, nb, synth, torch, np) -> int:
         # the whole workload is well under a second of CPU work, so the sample is all of it
         nb_s = B
         t0 = time.perf_counter()
-        oracle.attn_cross16(q[:nb_s], k[:nb_s], v[:nb_s], synth.BF16, True, scale)
+        if fp8:
+            oracle.attn_cross_e4m3(q[:nb_s], k[:nb_s], v[:nb_s], FP8_DESCALE["q"], FP8_DESCALE["k"], FP8_DESCALE["v"],
+                                   True, scale)
+        else:
+            oracle.attn_cross16(q[:nb_s], k[:nb_s], v[:nb_s], synth.BF16, True, scale)
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": nbytes * nb_s / B / dt / 1e9, "unit": "GB/s", "cores": int(oracle.threads()),
                                "kind": "oracle", "sample": "%d of %d batch entries, %.2f s wall incl. fp64 decode of K,V"
@@ -273,7 +293,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="long", help="tiny|encoder|prefill|gqa|long; long_d256 (the long shape at "
-                    "D = 256); decode (a second, HBM-bound path: naut_attn_decode); long_fp8 (the long shape on "
+                    "D = 256); decode (a second, HBM-bound path: naut_attn_decode); decode_fp8 (the same on an E4M3 cache: "
+                    "naut_attn_decode_fp8); long_fp8 (the long shape on "
                     "FP8 E4M3 inputs: naut_attn_fwd_fp8)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="seconds of CPU work the oracle baseline sample is sized for (0 = skip)")
@@ -310,6 +331,8 @@ def main() -> int:
 
     if args.workload == "decode":
         return bench_decode(args, nb, synth, torch, np)
+    if args.workload == "decode_fp8":
+        return bench_decode(args, nb, synth, torch, np, fp8=True)
     if args.workload == "long_fp8":
         return bench_fp8(args, nb, synth, torch, np)
 
