@@ -107,6 +107,25 @@ def test_moving_reference_maximum_wide(kind):
         gu.check(o, lse, o_ref, lse_ref, "wide/" + kind)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("variant", ["w8q32", "bm128"])
+def test_every_tile_count(variant, causal, monkeypatch):
+    """Sequence lengths just below, at and just above every multiple of 64 up to 704: every residue of the key-tile
+    count modulo the unrolled loops' period (4 LDS buffers in the 256-query kernel, 2 in the 128-query one), with
+    and without a ragged last tile, and every position of the causal diagonal inside a 256-query work-group."""
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", variant)
+    B, Hq, Hkv, D, idt, odt = 1, 2, 1, 128, synth.BF16, synth.F32
+    scale = 1.0 / math.sqrt(D)
+    for t in range(1, 12):
+        for S in (64 * t - 1, 64 * t, 64 * t + 1):
+            q = synth.fill(B, Hq, S, D, 6000 + S, synth.TAG_Q, idt)
+            k = synth.fill(B, Hkv, S, D, 6000 + S, synth.TAG_K, idt, S // 50, 8.0)
+            v = synth.fill(B, Hkv, S, D, 6000 + S, synth.TAG_V, idt)
+            o, lse = gu.run_hip(q, k, v, idt, odt, causal, scale)
+            o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal, scale)
+            gu.check(o, lse, o_ref, lse_ref, "S=%d %s causal=%d" % (S, variant, causal))
+
+
 VARIANT_SHAPES = [
     (1, 2, 1, 1, 64, True, synth.BF16, synth.BF16),
     (2, 4, 2, 129, 128, True, synth.BF16, synth.BF16),
