@@ -705,15 +705,6 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             qf[hf][ks] = ks * 2 + h < cpr ? *(const i32x4_t*)(qg + (size_t)q_ld * p.q_rs + ks * 32 + h * 16)
                                           : i32x4_t{0, 0, 0, 0};
     }
-#pragma unroll
-    for (int hf = 0; hf < QH; ++hf)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            if constexpr (ALLV)
-                asm volatile("" : "+v"(qf[hf][ks]));
-            else
-                asm volatile("" : "+a"(qf[hf][ks]));
-
     // Key range of this wavefront / this work-group (keys at or beyond kv_end_w are dead for it).
     const int kv_end_wg = CAUSAL ? (S < (qt + 1) * BM2 ? S : (qt + 1) * BM2) : S;
     const int kv_end_w = Q0 >= S ? 0 : (CAUSAL ? (S < Q0 + WQ ? S : Q0 + WQ) : S);
@@ -1082,6 +1073,16 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         for (int i = 0; i < LD_PER_W; ++i)
             issue_load(tv, i, v_goff);
     }
+    // Q is pinned to its registers only here: its loads, issued at the top, and the tile loads share one
+    // round trip to memory instead of taking one each.
+#pragma unroll
+    for (int hf = 0; hf < QH; ++hf)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            if constexpr (ALLV)
+                asm volatile("" : "+v"(qf[hf][ks]));
+            else
+                asm volatile("" : "+a"(qf[hf][ks]));
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -1194,33 +1195,79 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     if (Q0 >= S)
         return;
     constexpr int OUTB = DT_OUT == NAUT_F32 ? 4 : 2;
+    unsigned char* const o_bh = (unsigned char*)p.o + b * p.o_bs + hq * p.o_hs;
+    if constexpr (OUTB == 2) {
+        // 16-bit output goes through LDS so that it leaves in whole rows: a lane owns 4 consecutive
+        // d of one query (8 bytes, 32 different rows per store instruction); after the exchange 16
+        // lanes (D = 128) write one 256-byte row with 16 bytes each.  The staging rows live in this
+        // wavefront's own part of the first four tile buffers (where only its own tile loads land,
+        // and those are complete), so no barrier is needed: the other wavefronts have consumed every
+        // tile by the time this one is past the last barrier.
+        constexpr int CPRO = D / 8;           // 16-byte chunks per staged row
+        constexpr int PS = LD_PER_W * 1024;   // this wavefront's part of one tile buffer
+        constexpr int RP = PS / ROWB;         // staged rows per part
+        constexpr int R256 = ROWB >= 256 ? 1 : 256 / ROWB;  // rows per 256-byte bank line
+        static_assert(WQ / RP <= 2 * NBUF && WQ % RP == 0, "staging rows must fit this wavefront's tile parts");
+        auto staged = [&](int r, int ch) {  // chunk ch of staged row r; swizzled so that neither side conflicts
+            return smem + (r / RP) * TILEB + wave * PS + (r % RP) * ROWB + ((ch ^ ((r / R256) & (CPRO - 1))) << 4);
+        };
 #pragma unroll
-    for (int hf = 0; hf < QH; ++hf) {
-        const int q = qrow[hf];
-        const float lt = half_sum(l_run[hf]);
-        if (q >= S)
-            continue;
-        const float inv_l = 1.0f / lt;
-        if (p.lse != nullptr && h == 0)
-            p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
-        unsigned char* og = (unsigned char*)p.o + b * p.o_bs + hq * p.o_hs + (size_t)q * p.o_rs;
+        for (int hf = 0; hf < QH; ++hf) {
+            const int q = qrow[hf];
+            const float lt = half_sum(l_run[hf]);
+            const float inv_l = 1.0f / lt;  // rows beyond S: staged, never stored
+            if (p.lse != nullptr && h == 0 && q < S)
+                p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = 32 * db + 8 * g + 4 * h;
-                if (d >= cpr * 8)
-                    continue;  // padding columns of a narrower head dimension
-                const float x0 = oacc[hf][db][4 * g + 0] * inv_l, x1 = oacc[hf][db][4 * g + 1] * inv_l;
-                const float x2 = oacc[hf][db][4 * g + 2] * inv_l, x3 = oacc[hf][db][4 * g + 3] * inv_l;
-                if constexpr (DT_OUT == NAUT_F32) {
-                    f32x4_t w = {x0, x1, x2, x3};
-                    *(f32x4_t*)(og + d * 4) = w;
-                } else {
+                for (int g = 0; g < 4; ++g) {
+                    const int d = 32 * db + 8 * g + 4 * h;
+                    const float x0 = oacc[hf][db][4 * g + 0] * inv_l, x1 = oacc[hf][db][4 * g + 1] * inv_l;
+                    const float x2 = oacc[hf][db][4 * g + 2] * inv_l, x3 = oacc[hf][db][4 * g + 3] * inv_l;
                     i32x2_t w = {In<DT_OUT>::pack2(x0, x1), In<DT_OUT>::pack2(x2, x3)};
-                    *(i32x2_t*)(og + d * 2) = w;
+                    *(i32x2_t*)(staged(32 * hf + l32, d >> 3) + (d & 7) * 2) = w;
                 }
-            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        constexpr int RPI = 64 / CPRO;  // rows per store instruction
+        typedef i32x4_t __attribute__((aligned(8))) i32x4_a8;  // O rows are 8-byte aligned, not more
+        i32x4_t rows[WQ / RPI];
+#pragma unroll
+        for (int i = 0; i < WQ / RPI; ++i)  // all reads first: one LDS latency, not one per store
+            rows[i] = *(const i32x4_t*)staged(i * RPI + lane / CPRO, lane % CPRO);
+#pragma unroll
+        for (int i = 0; i < WQ / RPI; ++i) {
+            const int ch = lane % CPRO;
+            const int q = Q0 + i * RPI + lane / CPRO;
+            if (q < S && ch < cpr)  // not the rows beyond S, not the padding columns of a narrower head
+                *(i32x4_a8*)(o_bh + (size_t)q * p.o_rs + ch * 16) = rows[i];
+        }
+    } else {
+#pragma unroll
+        for (int hf = 0; hf < QH; ++hf) {
+            const int q = qrow[hf];
+            const float lt = half_sum(l_run[hf]);
+            if (q >= S)
+                continue;
+            const float inv_l = 1.0f / lt;
+            if (p.lse != nullptr && h == 0)
+                p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
+            unsigned char* og = o_bh + (size_t)q * p.o_rs;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int d = 32 * db + 8 * g + 4 * h;
+                    if (d >= cpr * 8)
+                        continue;  // padding columns of a narrower head dimension
+                    f32x4_t w = {oacc[hf][db][4 * g + 0] * inv_l, oacc[hf][db][4 * g + 1] * inv_l,
+                                 oacc[hf][db][4 * g + 2] * inv_l, oacc[hf][db][4 * g + 3] * inv_l};
+                    *(f32x4_t*)(og + d * 4) = w;
+                }
+        }
     }
 }
 
