@@ -701,9 +701,13 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     for (int hf = 0; hf < QH; ++hf) {
         const int q_ld = qrow[hf] < S ? qrow[hf] : S - 1;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            qf[hf][ks] = ks * 2 + h < cpr ? *(const i32x4_t*)(qg + (size_t)q_ld * p.q_rs + ks * 32 + h * 16)
-                                          : i32x4_t{0, 0, 0, 0};
+        for (int ks = 0; ks < KS; ++ks) {
+            // Unconditional, from a chunk that exists; the padding chunks of a narrower head are zeroed
+            // when Q is pinned below.  (A load under a condition becomes a branch, and the compiler then
+            // waited for the first loads in the middle of issuing the rest.)
+            const int ch = ks * 2 + h < cpr ? ks * 2 + h : cpr - 1;
+            qf[hf][ks] = *(const i32x4_t*)(qg + (size_t)q_ld * p.q_rs + ch * 16);
+        }
     }
     // Key range of this wavefront / this work-group (keys at or beyond kv_end_w are dead for it).
     const int kv_end_wg = CAUSAL ? (S < (qt + 1) * BM2 ? S : (qt + 1) * BM2) : S;
@@ -1075,14 +1079,19 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     }
     // Q is pinned to its registers only here: its loads, issued at the top, and the tile loads share one
     // round trip to memory instead of taking one each.
+    int cpr_late = cpr;
+    asm volatile("" : "+s"(cpr_late));  // ordered after the tile loads above: so is everything that uses it
 #pragma unroll
     for (int hf = 0; hf < QH; ++hf)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks * 2 + h >= cpr_late)
+                qf[hf][ks] = i32x4_t{0, 0, 0, 0};
             if constexpr (ALLV)
                 asm volatile("" : "+v"(qf[hf][ks]));
             else
                 asm volatile("" : "+a"(qf[hf][ks]));
+        }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
