@@ -29,8 +29,8 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16/fp16 MFMA: 256 CU x 4096 FLOP/clk
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a plain
 # copy kernel of known size; filled in from profiles/ once measured, else null.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/naut_fwd_bm256_w8q32_long_S16384_D128_causal.md: 718190 KiB x 2.000 read + 133230 KiB x 1.000 written
-    "long": 1.607e9,
+    # profiles/naut_fwd_bm256_w8q32_long_S16384_D128_causal.md: 721930 KiB x 2.000 read + 133120 KiB x 1.000 written
+    "long": 1.615e9,
     # profiles/naut_decode_B8_Hq32_Hkv8_Sk16384_D128.md: (262347 + 407) KiB x 2.000 read + (528 + 72) KiB written
     "decode": 5.387e8,
     # profiles/naut_fwd_fp8_long_S16384_D128_causal.md: 564080 KiB x 2.000 read + 133170 KiB written
