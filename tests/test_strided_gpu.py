@@ -85,6 +85,26 @@ def test_padded_rows_and_untouched_gaps():
     assert torch.all(o_buf[..., D:] == 7.0).item(), "the gaps between O rows were written"
 
 
+@pytest.mark.parametrize("variant", ["w8q32", "w4q64", "bm128"])
+@pytest.mark.parametrize("D,odt", [(128, synth.BF16), (64, synth.F16), (80, synth.BF16)])
+def test_o_rows_aligned_to_8_bytes_only(D, odt, variant, monkeypatch):
+    """16-bit O with a row pitch of D + 4 elements: rows start on 8-byte, not 16-byte, boundaries (the least the
+    entry point accepts), the S = 333 rows end in a ragged tile, and the 4-element gaps must stay untouched.
+    The pipelined kernels write O in 16-byte pieces of whole rows, so this is their unaligned-store case."""
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", variant)
+    B, Hq, Hkv, S = 2, 4, 2, 333
+    idt = odt
+    q, k, v = make(B, Hq, Hkv, S, D, idt, 9300 + D)
+    scale = 1.0 / math.sqrt(D)
+    qd, kd, vd = (gu.to_device(a, idt) for a in (q, k, v))
+    o_buf = torch.full((B, Hq, S, D + 4), 7.0, dtype=gu.TORCH_DT[odt], device="cuda")
+    print("8-byte O rows", D, variant, flush=True)
+    o, lse = run_strided(qd, kd, vd, o_buf[..., :D], True, scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale)
+    gu.check(o, lse, o_ref, lse_ref, "8-byte O rows D=%d %s" % (D, variant))
+    assert torch.all(o_buf[..., D:] == 7.0).item(), "the gaps between O rows were written"
+
+
 def test_broadcast_kv_over_batch():
     """Stride 0 on the batch axis of K and V: one cache shared by every batch entry."""
     B, Hq, Hkv, S, D = 3, 4, 4, 200, 64
