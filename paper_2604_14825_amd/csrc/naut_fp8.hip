@@ -315,20 +315,49 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     // Epilogue: one division by l (the 2^7 of P cancels), times descale_v; lse undoes the shift.
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv_l = p.dv / l_tot;
-    if (my_q < S) {
-        if (p.lse != nullptr && h == 0)
-            p.lse[(size_t)bh * S + my_q] = (m_run - F8_P_SHIFT + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
-        unsigned char* og = (unsigned char*)p.o +
-                            (STRIDED ? b * p.o_bs + hq * p.o_hs : (long long)bh * S * D * 2) + (size_t)my_q * o_rs;
+    if (my_q < S && p.lse != nullptr && h == 0)
+        p.lse[(size_t)bh * S + my_q] = (m_run - F8_P_SHIFT + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+    // O leaves through LDS in whole rows: a lane owns 4 consecutive d of one query (8 bytes, 32 different
+    // rows per store instruction); after the exchange D/8 lanes write one row with 16 bytes each.  The tiles
+    // are dead after the loop's last barrier; each wavefront stages its 32 rows in its own quarter of them.
+    {
+        constexpr int ROWB_O = D * 2, CPRO = D / 8, R256 = ROWB_O >= 256 ? 1 : 256 / ROWB_O;
+        static_assert(F8_WAVES * 32 * ROWB_O <= 4 * TILEB, "staging rows must fit the tile buffers");
+        // Every address below derives from this copy of the lane id, which exists only from here on: nothing
+        // of the epilogue can be computed before the key loop and held in registers across it.
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int l32e = ln & 31, he = ln >> 5;
+        unsigned char* const stg = smem + wave * 32 * ROWB_O;
+        auto staged = [&](int r, int ch) {  // swizzled so that neither the writes nor the reads conflict
+            return stg + r * ROWB_O + ((ch ^ ((r / R256) & (CPRO - 1))) << 4);
+        };
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int d = 32 * db + 8 * g + 4 * h;
+                const int d = 32 * db + 8 * g + 4 * he;
                 const i32x2_t w = {In<NAUT_BF16>::pack2(oacc[db][4 * g + 0] * inv_l, oacc[db][4 * g + 1] * inv_l),
                                    In<NAUT_BF16>::pack2(oacc[db][4 * g + 2] * inv_l, oacc[db][4 * g + 3] * inv_l)};
-                *(i32x2_t*)(og + d * 2) = w;
+                *(i32x2_t*)(staged(l32e, d >> 3) + (d & 7) * 2) = w;
             }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        constexpr int RPI = 64 / CPRO;  // rows per store instruction
+        typedef i32x4_t __attribute__((aligned(8))) i32x4_a8;  // O rows are 8-byte aligned, not more
+        unsigned char* const o_bh =
+            (unsigned char*)p.o + (STRIDED ? b * p.o_bs + hq * p.o_hs : (long long)bh * S * D * 2);
+        i32x4_t rows[32 / RPI];
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i)
+            rows[i] = *(const i32x4_t*)staged(i * RPI + ln / CPRO, ln % CPRO);
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int q = q_wave0 + i * RPI + ln / CPRO;
+            if (q < S)
+                *(i32x4_a8*)(o_bh + (size_t)q * o_rs + (ln % CPRO) * 16) = rows[i];
+        }
     }
 }
 
