@@ -510,11 +510,55 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     // Epilogue: one division by l (the per-step divide/multiply pairs telescope away), lse, store.
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv_l = 1.0f / l_tot;
-    if (my_q < S) {
-        if (p.lse != nullptr && h == 0)
-            p.lse[(size_t)bh * S + my_q] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
-        constexpr int OUTB = DT_OUT == NAUT_F32 ? 4 : 2;
-        unsigned char* og = (unsigned char*)p.o + b * p.o_bs + hq * p.o_hs + (size_t)my_q * p.o_rs;
+    if (my_q < S && p.lse != nullptr && h == 0)
+        p.lse[(size_t)bh * S + my_q] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+    unsigned char* const o_bh = (unsigned char*)p.o + b * p.o_bs + hq * p.o_hs;
+    if constexpr (DT_OUT != NAUT_F32) {
+        // 16-bit O leaves through LDS in whole rows: a lane owns 4 consecutive d of one query (8 bytes, 32
+        // different rows per store instruction); after the exchange D/8 lanes write one row with 16 bytes
+        // each.  The tiles are dead after the loop's last barrier (every tile load has landed, every
+        // fragment has been consumed); each wavefront stages its 32 rows in its own part of them.
+        constexpr int CPRO = D / 8, R256 = ROWB >= 256 ? 1 : 256 / ROWB;
+        static_assert(NWAVES * 32 * ROWB <= (int)sizeof(smem), "staging rows must fit the tile buffers");
+        // Every address below derives from this copy of the lane id, which exists only from here on: nothing
+        // of the epilogue can be computed before the key loop and held in registers across it.
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int l32e = ln & 31, he = ln >> 5;
+        unsigned char* const stg = smem + wave * 32 * ROWB;
+        auto staged = [&](int r, int ch) {  // swizzled so that neither the writes nor the reads conflict
+            return stg + r * ROWB + ((ch ^ ((r / R256) & (CPRO - 1))) << 4);
+        };
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int d = 32 * db + 8 * g + 4 * he;
+                const i32x2_t w = {In<DT_OUT>::pack2(oacc[db][4 * g + 0] * inv_l, oacc[db][4 * g + 1] * inv_l),
+                                   In<DT_OUT>::pack2(oacc[db][4 * g + 2] * inv_l, oacc[db][4 * g + 3] * inv_l)};
+                *(i32x2_t*)(staged(l32e, d >> 3) + (d & 7) * 2) = w;
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        constexpr int RPI = 64 / CPRO;    // rows per store instruction
+        constexpr int BATCH = 8 < 32 / RPI ? 8 : 32 / RPI;  // reads in flight before their stores
+        typedef i32x4_t __attribute__((aligned(8))) i32x4_a8;  // O rows are 8-byte aligned, not more
+#pragma unroll
+        for (int i0 = 0; i0 < 32 / RPI; i0 += BATCH) {
+            i32x4_t rows[BATCH];
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i)
+                rows[i] = *(const i32x4_t*)staged((i0 + i) * RPI + ln / CPRO, ln % CPRO);
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                const int q = q_wave0 + (i0 + i) * RPI + ln / CPRO;
+                if (q < S && ln % CPRO < cpr)  // not the rows beyond S, not the padding columns of a narrower head
+                    *(i32x4_a8*)(o_bh + (size_t)q * p.o_rs + (ln % CPRO) * 16) = rows[i];
+            }
+        }
+    } else if (my_q < S) {
+        unsigned char* og = o_bh + (size_t)my_q * p.o_rs;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -522,15 +566,9 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                 const int d = 32 * db + 8 * g + 4 * h;
                 if (d >= cpr * 8)
                     continue;  // padding columns of a narrower head dimension
-                const float x0 = oacc[db][4 * g + 0] * inv_l, x1 = oacc[db][4 * g + 1] * inv_l;
-                const float x2 = oacc[db][4 * g + 2] * inv_l, x3 = oacc[db][4 * g + 3] * inv_l;
-                if constexpr (DT_OUT == NAUT_F32) {
-                    f32x4_t w = {x0, x1, x2, x3};
-                    *(f32x4_t*)(og + d * 4) = w;
-                } else {
-                    i32x2_t w = {In<DT_OUT>::pack2(x0, x1), In<DT_OUT>::pack2(x2, x3)};
-                    *(i32x2_t*)(og + d * 2) = w;
-                }
+                f32x4_t w = {oacc[db][4 * g + 0] * inv_l, oacc[db][4 * g + 1] * inv_l,
+                             oacc[db][4 * g + 2] * inv_l, oacc[db][4 * g + 3] * inv_l};
+                *(f32x4_t*)(og + d * 4) = w;
             }
     }
 }
