@@ -193,22 +193,32 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     // Q^T fragments (MFMA B operand): lane holds q[my_q][16*ks + 8*h .. +8].
     i32x4_t qf[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = ks * 2 + h < cpr ? *(const i32x4_t*)(qg + (size_t)my_q_ld * p.q_rs + ks * 32 + h * 16)
-                                  : i32x4_t{0, 0, 0, 0};
+    for (int ks = 0; ks < KS; ++ks) {
+        // Unconditional, from a chunk that exists (a load under a condition becomes a branch); the padding
+        // chunks of a narrower head are zeroed when Q is pinned.
+        const int ch = ks * 2 + h < cpr ? ks * 2 + h : cpr - 1;
+        qf[ks] = *(const i32x4_t*)(qg + (size_t)my_q_ld * p.q_rs + ch * 16);
+    }
     // Keep Q resident: without this the compiler re-issues the global loads inside the key loop.
-    // The wide instantiation keeps it, and O, in the accumulation registers.
+    // The wide instantiation keeps it, and O, in the accumulation registers.  D <= 128 pins it only
+    // after the first tile's loads are out, so that the two share one round trip to memory.
     auto pin_acc = [](f32x16_t& x) {
         if constexpr (WIDE)
             asm volatile("" : "+a"(x));
     };
+    auto pin_q = [&](int cpr_now) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        if constexpr (WIDE)
-            asm volatile("" : "+a"(qf[ks]));
-        else
-            asm volatile("" : "+v"(qf[ks]));
-    }
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks * 2 + h >= cpr_now)
+                qf[ks] = i32x4_t{0, 0, 0, 0};
+            if constexpr (WIDE)
+                asm volatile("" : "+a"(qf[ks]));
+            else
+                asm volatile("" : "+v"(qf[ks]));
+        }
+    };
+    if constexpr (WIDE)
+        pin_q(cpr);
 
     const int kv_end = CAUSAL ? (S < (qt + 1) * BM ? S : (qt + 1) * BM) : S;
     const int ntiles = (kv_end + BN - 1) / BN;
@@ -360,6 +370,9 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         asm volatile("s_barrier" ::: "memory");
     } else {
         g_load(0);
+        int cpr_late = cpr;
+        asm volatile("" : "+s"(cpr_late));  // ordered after the asm inside g_load: so is everything that uses it
+        pin_q(cpr_late);
         s_store(std::integral_constant<int, 0>{});
         __syncthreads();
     }
