@@ -1353,11 +1353,12 @@ inline int pick_variant(int S, long long nbh, int D, int causal)
     // 256..16384, 2..512 heads, both head dimensions, with and without the causal mask.  The
     // pipelined 256-query kernel halves the K/V traffic per FLOP but pays a fill and a drain stage
     // per work-group and needs a full wave of work-groups: it wins once there is one work-group per
-    // CU and the key loop is long enough (average keys per query times D above 2^16).  The
-    // 64-queries-per-wavefront variant was never the fastest and is selectable by name only.
+    // CU and the key loop is long enough (average keys per query: 512 and up at D = 128, above 1024
+    // at D = 64).  The 64-queries-per-wavefront variant was never the fastest and is selectable by
+    // name only.
     const long long wg256 = nbh * ((S + BM2 - 1) / BM2);
     const long long loop_work = (long long)(causal ? (S + 1) / 2 : S) * D;
-    return (wg256 >= 256 && loop_work > 65536) ? V_W8Q32 : V_BM128;
+    return (wg256 >= 256 && loop_work >= (D > 64 ? 65536 : 65537)) ? V_W8Q32 : V_BM128;
 }
 
 template <int D, int DT_IN, int DT_OUT>
