@@ -105,6 +105,23 @@ def test_o_rows_aligned_to_8_bytes_only(D, odt, variant, monkeypatch):
     assert torch.all(o_buf[..., D:] == 7.0).item(), "the gaps between O rows were written"
 
 
+@pytest.mark.parametrize("D,odt", [(256, synth.BF16), (200, synth.F16), (136, synth.BF16)])
+def test_o_rows_aligned_to_8_bytes_only_wide(D, odt):
+    """The same on the 256-wide kernel (two O rows per store instruction, 25 or 17 of the 32 chunks real at
+    D = 200 and 136)."""
+    B, Hq, Hkv, S = 1, 4, 2, 333
+    idt = odt
+    q, k, v = make(B, Hq, Hkv, S, D, idt, 9400 + D)
+    scale = 1.0 / math.sqrt(D)
+    qd, kd, vd = (gu.to_device(a, idt) for a in (q, k, v))
+    o_buf = torch.full((B, Hq, S, D + 4), 7.0, dtype=gu.TORCH_DT[odt], device="cuda")
+    print("8-byte O rows, wide kernel", D, flush=True)
+    o, lse = run_strided(qd, kd, vd, o_buf[..., :D], True, scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale)
+    gu.check(o, lse, o_ref, lse_ref, "8-byte O rows D=%d" % D)
+    assert torch.all(o_buf[..., D:] == 7.0).item(), "the gaps between O rows were written"
+
+
 def test_broadcast_kv_over_batch():
     """Stride 0 on the batch axis of K and V: one cache shared by every batch entry."""
     B, Hq, Hkv, S, D = 3, 4, 4, 200, 64
