@@ -96,17 +96,19 @@ def test_fp8_growing_keys_and_bit_identity():
     check(o, lse, o_ref, lse_ref, v, "fp8 ascending keys")
 
 
+@pytest.mark.parametrize("pad", [32, 4])
 @pytest.mark.parametrize("B,Hq,Hkv,S,D,causal", [(2, 6, 2, 300, 128, True), (1, 4, 4, 777, 64, False),
                                                  (2, 8, 2, 129, 128, False)])
-def test_fp8_sequence_major_layout(B, Hq, Hkv, S, D, causal):
+def test_fp8_sequence_major_layout(B, Hq, Hkv, S, D, causal, pad):
     """Tensors stored [B][S][H][D], passed as transposed views; O (rows padded to a wider pitch) written in the
-    same layout, its gaps untouched."""
+    same layout, its gaps untouched.  pad = 4: O rows start on 8-byte boundaries only, the least the entry point
+    accepts (the kernel writes O in 16-byte pieces)."""
     q, k, v = make(B, Hq, Hkv, S, D, 11300 + S + D, S // 50)
     scale = 1.0 / math.sqrt(D)
     bshd = lambda a: torch.from_numpy(np.ascontiguousarray(a.transpose(0, 2, 1, 3))).cuda().transpose(1, 2)
     qd, kd, vd = bshd(q), bshd(k), bshd(v)
     assert not kd.is_contiguous()
-    P = D + 32
+    P = D + pad
     o_mem = torch.full((B, S, Hq, P), 7.0, dtype=torch.bfloat16, device="cuda")
     od = o_mem[..., :D].transpose(1, 2)
     lse = torch.full((B, Hq, S), float("nan"), dtype=torch.float32, device="cuda")
