@@ -620,6 +620,14 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
 #ifndef NAUT_ABLATE
 #define NAUT_ABLATE 0
 #endif
+#ifndef NAUT_STAMP
+#define NAUT_STAMP 0
+#endif
+// Timing-only build (NAUT_STAMP=1; paper_2604_14825_amd/wgtrace.py reads it): every wavefront of the
+// pipelined kernel stamps the constant 100 MHz clock at six points of its life and writes the stamps, the
+// compute unit it ran on and its iteration count over the first 128 floats of its work-group's lse rows, in
+// place of lse.  O is still correct.
+constexpr bool STAMP = NAUT_STAMP != 0;
 constexpr int ABL = NAUT_ABLATE;  // timing experiments only (results are wrong when non-zero): 1 no softmax, 2 no LDS reads, 4 no barrier, 8 no tile loads, 128 tile loads of one address
 #ifndef NAUT_HAO
 #define NAUT_HAO 8
@@ -705,6 +713,9 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int h = lane >> 5;
+    unsigned long long ts[6] = {0, 0, 0, 0, 0, 0};
+    if constexpr (STAMP)
+        ts[0] = wall_clock64();  // entry
 
     // Tile scheduler.  Work-groups are dealt to the 8 XCDs round-robin by block id, and each XCD has
     // its own L2.  Every XCD is given a contiguous run of (batch, head) pairs and works on
@@ -1143,8 +1154,12 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             else
                 asm volatile("" : "+a"(qf[hf][ks]));
         }
+    if constexpr (STAMP)
+        ts[1] = wall_clock64();  // Q and the prologue tiles issued
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if constexpr (STAMP)
+        ts[2] = wall_clock64();  // ... landed and published
 
     // s_e / s_o: scores of the current even / odd block; p_e / p_o: P of the last even / odd block
     f32x16_t s_e[QH], s_o[QH];
@@ -1228,6 +1243,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 iteration(UC, j);
         });
     }
+    if constexpr (STAMP)
+        ts[3] = wall_clock64();  // active iterations done
     for (int j = n_act; j < niter; ++j) {  // this wavefront's part of the remaining tiles, one barrier each
         const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA, (j + LA) % NBUF, k_goff, k_goff_last);
         const TileLoad vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1, (j + LA - 1) % NBUF, v_goff, v_goff_last);
@@ -1251,6 +1268,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             asm volatile("" ::"v"(sink[i]));
     }
 
+    if constexpr (STAMP)
+        ts[4] = wall_clock64();  // idle iterations (causal: waiting for the wavefronts below the diagonal) done
     // ---- epilogue ----
     if (Q0 >= S)
         return;
@@ -1276,7 +1295,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             const int q = qrow[hf];
             const float lt = half_sum(l_run[hf]);
             const float inv_l = 1.0f / lt;  // rows beyond S: staged, never stored
-            if (p.lse != nullptr && h == 0 && q < S)
+            if (!STAMP && p.lse != nullptr && h == 0 && q < S)
                 p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -1313,7 +1332,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             if (q >= S)
                 continue;
             const float inv_l = 1.0f / lt;
-            if (p.lse != nullptr && h == 0)
+            if (!STAMP && p.lse != nullptr && h == 0)
                 p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
             unsigned char* og = o_bh + (size_t)q * p.o_rs;
 #pragma unroll
@@ -1327,6 +1346,20 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                                  oacc[hf][db][4 * g + 2] * inv_l, oacc[hf][db][4 * g + 3] * inv_l};
                     *(f32x4_t*)(og + d * 4) = w;
                 }
+        }
+    }
+    if constexpr (STAMP) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the wavefront's stores have been acknowledged
+        ts[5] = wall_clock64();
+        if (lane == 0 && p.lse != nullptr && S % BM2 == 0) {  // 8 words per wavefront, 64-bit each
+            unsigned long long* rec = (unsigned long long*)(p.lse + (size_t)bh * S + (size_t)qt * BM2) + wave * 8;
+#pragma unroll
+            for (int i = 0; i < 6; ++i)
+                rec[i] = ts[i];
+            // hardware id registers: XCC_ID (hwreg 20) in the upper word, HW_ID (hwreg 4) in the lower
+            rec[6] = ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32) |
+                     (unsigned)__builtin_amdgcn_s_getreg(4 | (31 << 11));
+            rec[7] = (unsigned long long)niter;
         }
     }
 }
