@@ -196,6 +196,22 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
                          float descale_q, float descale_k, float descale_v,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * naut_attn_decode for callers that cannot allocate or pass a workspace: code recorded under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * naut_attn_decode (bf16 in and out, D = 64 or 128) without `workspace`: the split partials go to a
+ * 16 MiB array in the library's own static device memory, which every GPU the library runs on holds until
+ * the process ends.  Sizes whose partials (naut_attn_decode_workspace_bytes) exceed 16 MiB are rejected
+ * with NAUT_ERR_UNSUPPORTED and a message that names both numbers.  The call allocates and frees nothing;
+ * its first use on a device looks up the array's device address (hipGetSymbolAddress, once per device), so
+ * make that first call outside a graph capture.  All calls on one GPU share the one array, which keeps the
+ * last call's partials (every call overwrites all it reads, nothing needs clearing): calls that may overlap
+ * on one GPU -- different streams, or a graph replay beside eager calls -- race on it and must use
+ * naut_attn_decode with workspaces of their own.
+ */
+int naut_attn_decode_static(const void* q, const void* k, const void* v, void* o, float* lse,
+                            int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale, void* stream);
+
 /* Bytes of workspace naut_attn_decode[_dt|_strided] needs for these sizes; 0 if they are unsupported.  Host only. */
 size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D);
 

@@ -25,7 +25,8 @@ NAUT_F32 = 2
 
 EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
            "naut_attn_variant_name", "naut_attn_decode", "naut_attn_decode_dt", "naut_attn_decode_workspace_bytes",
-           "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided", "naut_attn_fwd_fp8_strided", "naut_attn_decode_fp8")
+           "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided", "naut_attn_fwd_fp8_strided", "naut_attn_decode_fp8",
+           "naut_attn_decode_static")
 
 
 class NautStrides(ctypes.Structure):
@@ -82,6 +83,8 @@ def lib():
         L.naut_attn_decode_strided.restype = ci
         L.naut_attn_decode_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci,
                                                ctypes.POINTER(NautStrides)]
+        L.naut_attn_decode_static.restype = ci
+        L.naut_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp]
         _lib = L
     return _lib
 
@@ -196,6 +199,36 @@ def naut_attn_decode(q, k, v, o, lse, causal: bool, scale: float, workspace, str
     else:
         rc = naut_attn_decode_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, Sq, Sk,
                                   D, causal, scale, workspace.data_ptr(), ws_bytes, stream.cuda_stream, in_dt, out_dt)
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())
+
+
+def naut_attn_decode_static_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale,
+                                stream_ptr) -> int:
+    """Direct call with integer device addresses; returns the status code."""
+    return int(lib().naut_attn_decode_static(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, int(causal),
+                                             float(scale), stream_ptr))
+
+
+def naut_attn_decode_static(q, k, v, o, lse, causal: bool, scale: float, stream=None):
+    """naut_attn_decode without a workspace argument (bf16 tensors; the library's static scratch holds the partials)."""
+    import torch
+    for t in (q, k, v, o):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16):
+            raise ValueError("q, k, v, o must be contiguous bf16 device tensors")
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    if tuple(k.shape) != (B, Hkv, Sk, D) or tuple(v.shape) != (B, Hkv, Sk, D) or tuple(o.shape) != (B, Hq, Sq, D):
+        raise ValueError("shape mismatch between q, k, v, o")
+    lse_ptr = None
+    if lse is not None:
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, Hq, Sq)):
+            raise ValueError("lse must be a contiguous fp32 device tensor [B,Hq,Sq]")
+        lse_ptr = lse.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    rc = naut_attn_decode_static_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, Sq,
+                                     Sk, D, causal, scale, stream.cuda_stream)
     if rc != NAUT_OK:
         raise NautError(rc, last_error_string())
 

@@ -15,6 +15,7 @@
 // memory, so they are simply rows 0..R-1 of a [R][D] matrix, taken 32 at a time.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
@@ -628,6 +629,41 @@ struct Plan {
     size_t ws_bytes;
 };
 
+// Scratch of naut_attn_decode_static: the split partials live in this file-scope device array instead of a
+// caller-provided workspace.  Every GPU the library runs on holds its own copy at its own address for the
+// life of the process.  In host code the array's name is only a handle for hipGetSymbolAddress: the device
+// address it returns (taken once per device, with that device current) is what kernels and copies get.
+constexpr size_t DEC_STATIC_BYTES = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[DEC_STATIC_BYTES];
+constexpr int DEC_MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[DEC_MAX_DEVICES];
+
+// Device address of `scratch` on the current device (NULL and an error message on failure).
+void* static_scratch(int* err)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        *err = fail_launch(e);
+        return nullptr;
+    }
+    if (dev < 0 || dev >= DEC_MAX_DEVICES) {
+        *err = fail(NAUT_ERR_UNSUPPORTED, "device ordinal beyond the library's per-device table");
+        return nullptr;
+    }
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            snprintf(g_err, sizeof g_err, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+            *err = NAUT_ERR_HIP;
+            return nullptr;
+        }
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // every thread computes the same value
+    }
+    return ptr;
+}
+
 bool make_plan(int B, int Hq, int Hkv, int Sq, int Sk, int D, Plan* pl)
 {
     const long long R = (long long)(Hq / Hkv) * Sq;
@@ -679,9 +715,16 @@ size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, 
     return pl.ws_bytes;
 }
 
-int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
-                             int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
-                             void* stream, int in_dtype, int out_dtype, const naut_strides* st)
+}  // extern "C"
+
+namespace {
+
+// The 16-bit decode path behind naut_attn_decode[_dt|_strided] and naut_attn_decode_static.  With
+// `use_static` the split partials go to the library's static device array instead of `workspace`; its
+// address is taken only after every argument check has passed (no HIP call before that).
+int decode_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                 int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
+                 bool use_static, void* stream, int in_dtype, int out_dtype, const naut_strides* st)
 {
     if (!q || !k || !v || !o)
         return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
@@ -703,12 +746,24 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
     Plan pl;
     if (!make_plan(B, Hq, Hkv, Sq, Sk, DK, &pl))
         return fail(NAUT_ERR_UNSUPPORTED, "shape exceeds the grid limits");
+    if (use_static)
+        workspace = nullptr;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)workspace) & 15)
         return fail(NAUT_ERR_ALIGN, "q, k, v, o and workspace must be 16-byte aligned");
     if ((uintptr_t)lse & 3)
         return fail(NAUT_ERR_ALIGN, "lse must be 4-byte aligned");
-    if (!workspace || workspace_bytes < pl.ws_bytes)
-        return fail(NAUT_ERR_SHAPE, "workspace is NULL or smaller than naut_attn_decode_workspace_bytes()");
+    if (use_static) {
+        if (pl.ws_bytes > DEC_STATIC_BYTES) {
+            snprintf(g_err, sizeof g_err,
+                     "these sizes need %zu bytes of split partials, more than the %zu-byte static scratch of "
+                     "naut_attn_decode_static: use naut_attn_decode with a workspace",
+                     pl.ws_bytes, DEC_STATIC_BYTES);
+            return NAUT_ERR_UNSUPPORTED;
+        }
+    } else {
+        if (!workspace || workspace_bytes < pl.ws_bytes)
+            return fail(NAUT_ERR_SHAPE, "workspace is NULL or smaller than naut_attn_decode_workspace_bytes()");
+    }
 
     naut_strides cs;  // contiguous q, o [B][Hq][Sq][D] and k, v [B][Hkv][Sk][D]
     cs.q_s = cs.k_s = cs.v_s = cs.o_s = D;
@@ -731,6 +786,12 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
         return fail(NAUT_ERR_UNSUPPORTED, "sequence stride too large");
     const int out_b = out_dtype == NAUT_F32 ? 4 : 2;
 
+    if (use_static) {  // every host-side check has passed: the first HIP calls of this path
+        int err = NAUT_OK;
+        workspace = static_scratch(&err);
+        if (workspace == nullptr)
+            return err;
+    }
     DecodeParams p;
     p.q = q;
     p.k = k;
@@ -778,6 +839,18 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
     NAUT_DEC(64, NAUT_F16, NAUT_F32)
 #undef NAUT_DEC
     return fail(NAUT_ERR_UNSUPPORTED, "no kernel for this (D, dtype) combination");
+}
+
+}  // namespace
+
+extern "C" {
+
+int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                             int Sq, int Sk, int D, int causal, float scale, void* workspace, size_t workspace_bytes,
+                             void* stream, int in_dtype, int out_dtype, const naut_strides* st)
+{
+    return decode_16bit(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale, workspace, workspace_bytes, false, stream,
+                        in_dtype, out_dtype, st);
 }
 
 int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
@@ -856,6 +929,15 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
     if (e != hipSuccess)
         return fail_launch(e);
     return NAUT_OK;
+}
+
+int naut_attn_decode_static(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                              int Sq, int Sk, int D, int causal, float scale, void* stream)
+{
+    if (D > 0 && D != 64 && D != 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    return decode_16bit(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale, nullptr, 0, true, stream, NAUT_BF16,
+                        NAUT_BF16, nullptr);
 }
 
 int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,

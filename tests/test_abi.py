@@ -123,6 +123,20 @@ def test_decode_argument_checks():
     assert dec(wsb=ws - 1) == nb.NAUT_ERR_SHAPE
     assert "workspace" in nb.last_error_string()
 
+    # the entry point without a workspace argument: the same checks, all of them before its first HIP call
+    def dec0(q=A, k=A, **kw):
+        a = dict(ok)
+        a.update(kw)
+        return nb.naut_attn_decode_static_raw(q, k, A, A, A, a["B"], a["Hq"], a["Hkv"], a["Sq"], a["Sk"], a["D"],
+                                              a["causal"], a["scale"], None)
+    assert dec0(q=None) == nb.NAUT_ERR_NULL
+    assert dec0(Sk=0) == nb.NAUT_ERR_SHAPE
+    assert dec0(Sq=5000) == nb.NAUT_ERR_SHAPE
+    assert dec0(D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert dec0(k=A + 8) == nb.NAUT_ERR_ALIGN
+    assert dec0(B=64, Hq=64, Hkv=64) == nb.NAUT_ERR_UNSUPPORTED   # partials beyond the 16 MiB static scratch
+    assert "static scratch" in nb.last_error_string()
+
     # strided variant: same stride rules as the strided prefill entry point
     bf = nb.NAUT_BF16
     B, Hq, Hkv, Sq, Sk, D = 1, 8, 2, 1, 4096, 128
