@@ -45,10 +45,11 @@ extern "C" {
 
 typedef enum {
     NAUT_OK = 0,
-    NAUT_ERR_NULL = -1,        /* q, k, v or o is NULL */
-    NAUT_ERR_SHAPE = -2,       /* a size <= 0, Hq % Hkv != 0, or scale not finite */
-    NAUT_ERR_UNSUPPORTED = -3, /* D not in {64,128}, unknown dtype pair, scale < 0, size beyond 32-bit grid limits */
-    NAUT_ERR_ALIGN = -4,       /* q/k/v/o not 16-byte aligned or lse not 4-byte aligned */
+    NAUT_ERR_NULL = -1,        /* q, k, v, o or a required workspace is NULL */
+    NAUT_ERR_SHAPE = -2,       /* a size <= 0, Hq % Hkv != 0, scale not finite, rows that overlap, workspace too small */
+    NAUT_ERR_UNSUPPORTED = -3, /* a head dimension the entry point does not take (each one states its set), unknown
+                                  dtype pair, scale < 0, sizes or strides beyond the 32-bit limits of a kernel */
+    NAUT_ERR_ALIGN = -4,       /* a pointer or stride off the alignment the entry point states */
     NAUT_ERR_HIP = -5          /* the launch failed; see naut_last_error_string() */
 } naut_status;
 
@@ -159,7 +160,7 @@ const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int 
  * instead of across steps); the partials live in `workspace`, DEVICE memory owned by the caller, 16-byte
  * aligned, of at least naut_attn_decode_workspace_bytes(...) bytes, which the call overwrites and
  * which must not be shared by calls that may overlap.  Two kernels are enqueued on `stream`; nothing
- * is allocated, nothing is synchronised.  Errors as above (a missing or short workspace is
+ * is allocated, nothing is synchronised.  Errors as above (a NULL workspace is NAUT_ERR_NULL, a short one
  * NAUT_ERR_SHAPE).
  */
 int naut_attn_decode(const void* q, const void* k, const void* v, void* o, float* lse,

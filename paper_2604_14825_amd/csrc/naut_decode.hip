@@ -761,8 +761,10 @@ int decode_16bit(const void* q, const void* k, const void* v, void* o, float* ls
             return NAUT_ERR_UNSUPPORTED;
         }
     } else {
-        if (!workspace || workspace_bytes < pl.ws_bytes)
-            return fail(NAUT_ERR_SHAPE, "workspace is NULL or smaller than naut_attn_decode_workspace_bytes()");
+        if (!workspace)
+            return fail(NAUT_ERR_NULL, "workspace must be a non-NULL device pointer");
+        if (workspace_bytes < pl.ws_bytes)
+            return fail(NAUT_ERR_SHAPE, "workspace is smaller than naut_attn_decode_workspace_bytes()");
     }
 
     naut_strides cs;  // contiguous q, o [B][Hq][Sq][D] and k, v [B][Hkv][Sk][D]
@@ -878,8 +880,10 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
         return fail(NAUT_ERR_ALIGN, "q, k, v, o and workspace must be 16-byte aligned");
     if ((uintptr_t)lse & 3)
         return fail(NAUT_ERR_ALIGN, "lse must be 4-byte aligned");
-    if (!workspace || workspace_bytes < pl.ws_bytes)
-        return fail(NAUT_ERR_SHAPE, "workspace is NULL or smaller than naut_attn_decode_workspace_bytes()");
+    if (!workspace)
+        return fail(NAUT_ERR_NULL, "workspace must be a non-NULL device pointer");
+    if (workspace_bytes < pl.ws_bytes)
+        return fail(NAUT_ERR_SHAPE, "workspace is smaller than naut_attn_decode_workspace_bytes()");
 
     DecodeParams p;
     p.q = q;

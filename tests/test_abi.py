@@ -119,7 +119,7 @@ def test_decode_argument_checks():
     assert dec(scale=-1.0) == nb.NAUT_ERR_UNSUPPORTED
     assert dec(D=96) == nb.NAUT_ERR_UNSUPPORTED
     assert dec(k=A + 8) == nb.NAUT_ERR_ALIGN
-    assert dec(wsp=None) == nb.NAUT_ERR_SHAPE
+    assert dec(wsp=None) == nb.NAUT_ERR_NULL
     assert dec(wsb=ws - 1) == nb.NAUT_ERR_SHAPE
     assert "workspace" in nb.last_error_string()
 
@@ -168,7 +168,7 @@ def test_decode_fp8_argument_checks():
     assert d8(dv=0.0) == nb.NAUT_ERR_UNSUPPORTED
     assert d8(D=96) == nb.NAUT_ERR_UNSUPPORTED
     assert d8(k=A + 8) == nb.NAUT_ERR_ALIGN
-    assert d8(wsp=None) == nb.NAUT_ERR_SHAPE
+    assert d8(wsp=None) == nb.NAUT_ERR_NULL
     assert d8(wsb=16) == nb.NAUT_ERR_SHAPE
 
 
