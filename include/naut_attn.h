@@ -216,6 +216,18 @@ int naut_attn_decode_static(const void* q, const void* k, const void* v, void* o
 /* Bytes of workspace naut_attn_decode[_dt|_strided] needs for these sizes; 0 if they are unsupported.  Host only. */
 size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D);
 
+/*
+ * Measurement aid, not part of the attention path (the paper's evaluation, Section 6, reports throughput
+ * against the hardware's capability; this gives the capability of the box at hand): a register-only loop of
+ * the matrix instruction the bf16 kernels use (v_mfma_f32_32x32x16_bf16), `work_groups` work-groups of 8
+ * wavefronts, each issuing trips * 16 of them = trips * 16 * 32768 FLOP per wavefront, with no LDS, memory
+ * or vector work beside them.  kind 0: all operands zero; kind 1: operands with random signs, fractions and
+ * a few binades of exponent, a fresh A operand every instruction -- the switching activity of real data,
+ * which decides how far the chip lowers its clock under sustained matrix load.  `out` (device memory,
+ * work_groups * 512 floats, overwritten) only keeps the loop alive.  Asynchronous on `stream`.
+ */
+int naut_probe_mfma(float* out, size_t out_floats, int work_groups, int trips, int kind, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ NAUT_F32 = 2
 EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
            "naut_attn_variant_name", "naut_attn_decode", "naut_attn_decode_dt", "naut_attn_decode_workspace_bytes",
            "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided", "naut_attn_fwd_fp8_strided", "naut_attn_decode_fp8",
-           "naut_attn_decode_static")
+           "naut_attn_decode_static", "naut_probe_mfma")
 
 
 class NautStrides(ctypes.Structure):
@@ -83,6 +83,8 @@ def lib():
         L.naut_attn_decode_strided.restype = ci
         L.naut_attn_decode_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci,
                                                ctypes.POINTER(NautStrides)]
+        L.naut_probe_mfma.restype = ci
+        L.naut_probe_mfma.argtypes = [vp, sz, ci, ci, ci, vp]
         L.naut_attn_decode_static.restype = ci
         L.naut_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp]
         _lib = L
@@ -419,3 +421,14 @@ def naut_attn_decode_fp8(q, k, v, o, lse, causal: bool, scale: float, descale_q:
                                   workspace.numel() * workspace.element_size(), stream.cuda_stream)
     if rc != NAUT_OK:
         raise NautError(rc, last_error_string())
+
+
+def naut_probe_mfma(out, work_groups: int, trips: int, kind: int, stream=None) -> float:
+    """Enqueue the register-only MFMA loop (see naut_probe_mfma in the header); returns the FLOPs it performs."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(out.device)
+    rc = int(lib().naut_probe_mfma(out.data_ptr(), out.numel(), work_groups, trips, kind, stream.cuda_stream))
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())
+    return float(work_groups) * 8 * trips * 16 * 32768

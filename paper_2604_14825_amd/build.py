@@ -11,7 +11,7 @@ _CSRC = os.path.join(_HERE, "csrc")
 # (source, extra defines, object name).  The prefill kernels are instantiated in naut_attn_inst.hip, compiled
 # once per (input type, output type) pair so that the four pairs build in parallel.
 _DT = {"bf16": 0, "f16": 1, "f32": 2}  # naut_dtype
-JOBS = [(os.path.join(_CSRC, n), [], n + ".o") for n in ("naut_attn.hip", "naut_decode.hip", "naut_fp8.hip")]
+JOBS = [(os.path.join(_CSRC, n), [], n + ".o") for n in ("naut_attn.hip", "naut_decode.hip", "naut_fp8.hip", "naut_probe.hip")]
 JOBS += [(os.path.join(_CSRC, "naut_attn_inst.hip"), ["-DNAUT_INST_IN=%d" % _DT[i], "-DNAUT_INST_OUT=%d" % _DT[o]],
           "naut_attn_inst_%s_%s.o" % (i, o))
          for i, o in (("bf16", "bf16"), ("bf16", "f32"), ("f16", "f16"), ("f16", "f32"))]

@@ -179,7 +179,8 @@ const char* naut_attn_variant_name(int B, int Hq, int S, int D, int causal, int 
         return nullptr;
     if (D == 256)
         return "fwd_bm128_w4q32_bn32";
-    return kVariantName[pick_variant(S, (long long)B * Hq, D, causal)];
+    const int variant = pick_variant(S, (long long)B * Hq, D, causal);
+    return variant < 0 ? nullptr : kVariantName[variant];
 }
 
 }  // extern "C"

@@ -243,27 +243,31 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     }
     // asm, so that the compiler does not make every later LDS read wait for these loads; completion
     // is awaited explicitly (vmcnt) before the barrier that publishes the tile.
+    // The address of a load is the tile's base, a 64-bit wave-uniform pointer, plus a 32-bit lane offset inside
+    // the tile (at most BN rows of the largest row stride the entry point admits); rows beyond the end of the
+    // sequence re-read its last row.
     auto issue_tile = [&](int tile) {
         const unsigned kd = smem_base + (unsigned)((tile % NB) * TILEB + wave * LDW * 1024);
         const unsigned vd = kd + NB * TILEB;
+        const unsigned char* const kt = kg + (size_t)tile * BN * p.k_rs;
+        const unsigned char* const vt = vg + (size_t)tile * BN * p.v_rs;
+        const int last_row = S - 1 - tile * BN;  // of this tile, counted from its first row; >= 0
 #pragma unroll
         for (int n = 0; n < LDW; ++n) {
-            int row = tile * BN + wk_row[n];
-            row = row < S ? row : S - 1;
+            const int row = wk_row[n] < last_row ? wk_row[n] : last_row;
             const int off = row * p.k_rs + wk_col[n];
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
-                         : "s"(kd + n * 1024), "v"(off), "s"(kg)
+                         : "s"(kd + n * 1024), "v"(off), "s"(kt)
                          : "memory", "m0");
         }
 #pragma unroll
         for (int n = 0; n < LDW; ++n) {
-            int row = tile * BN + wv_row[n];
-            row = row < S ? row : S - 1;
+            const int row = wv_row[n] < last_row ? wv_row[n] : last_row;
             const int off = row * p.v_rs + wv_col[n];
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
-                         : "s"(vd + n * 1024), "v"(off), "s"(vg)
+                         : "s"(vd + n * 1024), "v"(off), "s"(vt)
                          : "memory", "m0");
         }
     };
@@ -605,37 +609,15 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
 // size.  K and V tiles (64 keys) are multi-buffered in LDS and filled by direct global->LDS loads
 // issued LA tiles ahead, one barrier per tile.
 
-#ifndef NAUT_LA
-#define NAUT_LA 3
-#endif
 #ifndef NAUT_PF
 #define NAUT_PF 6
 #endif
-#ifndef NAUT_WPAIR
-#define NAUT_WPAIR 1
-#endif
-#ifndef NAUT_SPREAD
-#define NAUT_SPREAD 1
-#endif
-#ifndef NAUT_ABLATE
-#define NAUT_ABLATE 0
-#endif
-#ifndef NAUT_STAMP
-#define NAUT_STAMP 0
-#endif
-// Timing-only build (NAUT_STAMP=1; paper_2604_14825_amd/wgtrace.py reads it): every wavefront of the
-// pipelined kernel stamps the constant 100 MHz clock at six points of its life and writes the stamps, the
-// compute unit it ran on and its iteration count over the first 128 floats of its work-group's lse rows, in
-// place of lse.  O is still correct.
-constexpr bool STAMP = NAUT_STAMP != 0;
-constexpr int ABL = NAUT_ABLATE;  // timing experiments only (results are wrong when non-zero): 1 no softmax, 2 no LDS reads, 4 no barrier, 8 no tile loads, 128 tile loads of one address
 #ifndef NAUT_HAO
 #define NAUT_HAO 8
 #endif
 constexpr int HEADS_AT_ONCE = NAUT_HAO;
 constexpr int BM2 = 256;
-constexpr int LA = NAUT_LA;     // tile loads are issued this many iterations ahead of their use
-static_assert(LA == 3, "3 is the depth the unrolled key loop has been validated and measured with");
+constexpr int LA = 3;           // tile loads are issued this many iterations ahead of their use
 constexpr int NBUF = LA + 1;    // LDS buffers per operand
 constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no maximum yet": keeps -inf - (-inf) out
 
@@ -713,9 +695,6 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int h = lane >> 5;
-    unsigned long long ts[6] = {0, 0, 0, 0, 0, 0};
-    if constexpr (STAMP)
-        ts[0] = wall_clock64();  // entry
 
     // Tile scheduler.  Work-groups are dealt to the 8 XCDs round-robin by block id, and each XCD has
     // its own L2.  Every XCD is given a contiguous run of (batch, head) pairs and works on
@@ -836,7 +815,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         TileLoad t;
         const int tl = tile < ntiles ? tile : ntiles - 1;
         t.dst = lds_tiles + (unsigned)(buf * TILEB + wave * LD_PER_W * 1024);
-        t.gt = g + ((ABL & 128) ? (size_t)0 : (size_t)tl * BN * row_stride);
+        t.gt = g + (size_t)tl * BN * row_stride;
         if (tile >= ntiles - 1) {
 #pragma unroll
             for (int i = 0; i < LD_PER_W; ++i) {
@@ -848,23 +827,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     };
     // asm, so that the compiler does not make every later LDS read wait for these loads;
     // completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
-    i32x4_t sink[4];  // ablation 64 only: tile loads land in these dedicated registers instead of LDS
-    if constexpr ((ABL & 64) != 0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sink[i] = i32x4_t{0, 0, 0, 0};
-            asm volatile("" : "+v"(sink[i]));
-        }
-    }
     auto issue_load = [&](const TileLoad& t, int i, const int* goff) {
-        const int off = (ABL & 128) ? 0 : goff[i];
-        if constexpr ((ABL & 64) != 0) {
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(sink[i & 3]) : "v"(off), "s"(t.gt) : "memory");
-            return;
-        }
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
-                     : "s"(t.dst + i * 1024), "v"(off), "s"(t.gt)
+                     : "s"(t.dst + i * 1024), "v"(goff[i]), "s"(t.gt)
                      : "memory", "m0");
     };
     const unsigned k_lds = smem_base, v_lds = smem_base + NBUF * TILEB;
@@ -943,15 +909,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         constexpr bool next_iter = decltype(NEXT)::value;
         constexpr int KOFF = (next_iter ? (U + 1) % NBUF : U) * TILEB;
         constexpr int VOFF = (next_iter ? U : (U + NBUF - 1) % NBUF) * TILEB;
-        if constexpr ((ABL & 2) != 0) {
-            i32x4_t fr;
-            asm volatile("" : "=v"(fr));
-            return fr;
-        } else if constexpr (f % 2 == 0 && (ABL & 32) != 0) {  // timing only: V^T fragment as one plain 128-bit read
-            constexpr int y = f / 2, t = y / DB, db = y % DB;
-            const int a = k_it[db + 4 * t] + KOFF;
-            return *(const NAUT_LDS i32x4_t*)(uintptr_t)(a + BLK * 32 * ROWB + NBUF * TILEB);
-        } else if constexpr (f % 2 == 0) {
+        if constexpr (f % 2 == 0) {
             constexpr int y = f / 2, t = y / DB, db = y % DB;
             constexpr int off = (BLK * 32 + 16 * t) * ROWB;
             const int a = v_it[db] + VOFF;
@@ -1023,17 +981,16 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             constexpr int f = i / QH, hf = i % QH;
             if constexpr (hf == 0)
                 issue(std::integral_constant<int, f + PREFETCH>{});
-            const i32x4_t& fr_op = (ABL & 16) ? qf[0][0] : frag[f];  // ablation 16: the reads feed nothing
             if constexpr (f % 2 == 0) {
                 constexpr int y = f / 2, t = y / DB, db = y % DB;
-                oacc[hf][db] = T::mfma(fr_op, p_in[hf][t], oacc[hf][db]);
+                oacc[hf][db] = T::mfma(frag[f], p_in[hf][t], oacc[hf][db]);
             } else {
                 constexpr int ks = f / 2;
                 if constexpr (ALLV) {
                     if constexpr (ks == 0)
-                        s_nxt[hf] = T::mfma(fr_op, qf[hf][ks], f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f});
+                        s_nxt[hf] = T::mfma(frag[f], qf[hf][ks], f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f});
                     else
-                        s_nxt[hf] = T::mfma(fr_op, qf[hf][ks], s_nxt[hf]);
+                        s_nxt[hf] = T::mfma(frag[f], qf[hf][ks], s_nxt[hf]);
                 } else if constexpr (ks == 0)
                     XM::first(s_nxt[hf], frag[f], qf[hf][ks]);
                 else
@@ -1041,20 +998,14 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             }
             constexpr int p0 = PC::template begin<NS>(i), p1 = PC::template begin<NS>(i + 1);
             side(I);
-            if constexpr (!(ABL & 1))
-                static_for<p0, p1>([&](auto PCI) { piece(PCI); });
+            static_for<p0, p1>([&](auto PCI) { piece(PCI); });
             // one wait for two fragments: LDS reads return in order, so waiting at the end of an odd
             // slot for the fragment two slots on covers the next slot's too, and neither of the two
             // coming slots needs a wait instruction of its own
-            if constexpr (NAUT_WPAIR && hf == QH - 1 && f % 2 == 1 && f + 2 < NF)
+            if constexpr (hf == QH - 1 && f % 2 == 1 && f + 2 < NF)
                 asm volatile("" ::"v"(frag[f + 2]));
             __builtin_amdgcn_sched_barrier(0);
         });
-        if constexpr ((ABL & 16) != 0) {
-#pragma unroll
-            for (int f = 0; f < NF; ++f)
-                asm volatile("" ::"v"(frag[f]));
-        }
         bool over = false;  // also true for +inf (first block of a row: the reference is still M_INIT)
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf)
@@ -1154,12 +1105,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             else
                 asm volatile("" : "+a"(qf[hf][ks]));
         }
-    if constexpr (STAMP)
-        ts[1] = wall_clock64();  // Q and the prologue tiles issued
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if constexpr (STAMP)
-        ts[2] = wall_clock64();  // ... landed and published
 
     // s_e / s_o: scores of the current even / odd block; p_e / p_o: P of the last even / odd block
     f32x16_t s_e[QH], s_o[QH];
@@ -1194,25 +1141,15 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // wavefronts right after the barrier, which backs up the memory pipeline and stalls them.
         const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA, (U + LA) % NBUF, k_goff, k_goff_last);
         const TileLoad vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1, (U + LA - 1) % NBUF, v_goff, v_goff_last);
-        if constexpr (!(ABL & 8) && NAUT_SPREAD == 0) {
-#pragma unroll
-            for (int i = 0; i < LD_PER_W; ++i)
-                issue_load(kt, i, k_goff);
-#pragma unroll
-            for (int i = 0; i < LD_PER_W; ++i)
-                issue_load(vt, i, v_goff);
-        }
         auto side = [&](auto BLKC, auto I) {
             constexpr int BLK = decltype(BLKC)::value, i = decltype(I)::value;
             constexpr int NL = 2 * LD_PER_W, STEP = NS / NL;
-            if constexpr (!(ABL & 8) && NAUT_SPREAD != 0 && STEP > 0 && i % STEP == STEP / 2 && i / STEP < NL) {
+            if constexpr (BLK == 0 && STEP > 0 && i % STEP == STEP / 2 && i / STEP < NL) {
                 constexpr int q = i / STEP;
-                if (NAUT_SPREAD == 1 ? BLK == 0 : (wave & 1) == BLK) {
-                    if constexpr (q < LD_PER_W)
-                        issue_load(kt, q, k_goff);
-                    else
-                        issue_load(vt, q - LD_PER_W, v_goff);
-                }
+                if constexpr (q < LD_PER_W)
+                    issue_load(kt, q, k_goff);
+                else
+                    issue_load(vt, q - LD_PER_W, v_goff);
             }
         };
 
@@ -1226,15 +1163,13 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // The last slots of the next iteration already read the tiles of the one after it, so the
         // tiles issued LA-2 iterations ago must have landed by now; newer ones may fly on.
         static_assert(LA >= 2 && (LA - 2) * 2 * LD_PER_W < 64, "vmcnt field");
-        if constexpr (!(ABL & 256))  // ablation 256 (timing only): tiles are read without waiting for them
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
         // A bare barrier, not __syncthreads(): the fence in the latter would first drain the LDS
         // reads in flight, which are this wavefront's prefetch for the next stage.  They target
         // tiles published by the previous barrier and buffers that no load overwrites before the
         // barrier after this one, so they may stay in flight; the tile loads to be published have
         // been awaited just above.
-        if constexpr (!(ABL & 4))
-            asm volatile("s_barrier" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
     };
     for (int j0 = 0; j0 < n_act; j0 += NBUF) {
         static_for<0, NBUF>([&](auto UC) {
@@ -1243,33 +1178,20 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 iteration(UC, j);
         });
     }
-    if constexpr (STAMP)
-        ts[3] = wall_clock64();  // active iterations done
     for (int j = n_act; j < niter; ++j) {  // this wavefront's part of the remaining tiles, one barrier each
         const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA, (j + LA) % NBUF, k_goff, k_goff_last);
         const TileLoad vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1, (j + LA - 1) % NBUF, v_goff, v_goff_last);
-        if constexpr (!(ABL & 8)) {
 #pragma unroll
-            for (int i = 0; i < LD_PER_W; ++i)
-                issue_load(kt, i, k_goff);
+        for (int i = 0; i < LD_PER_W; ++i)
+            issue_load(kt, i, k_goff);
 #pragma unroll
-            for (int i = 0; i < LD_PER_W; ++i)
-                issue_load(vt, i, v_goff);
-        }
-        if constexpr (!(ABL & 256))
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
-        if constexpr (!(ABL & 4))
-            asm volatile("s_barrier" ::: "memory");
+        for (int i = 0; i < LD_PER_W; ++i)
+            issue_load(vt, i, v_goff);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
+        asm volatile("s_barrier" ::: "memory");
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if constexpr ((ABL & 64) != 0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            asm volatile("" ::"v"(sink[i]));
-    }
 
-    if constexpr (STAMP)
-        ts[4] = wall_clock64();  // idle iterations (causal: waiting for the wavefronts below the diagonal) done
     // ---- epilogue ----
     if (Q0 >= S)
         return;
@@ -1295,7 +1217,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             const int q = qrow[hf];
             const float lt = half_sum(l_run[hf]);
             const float inv_l = 1.0f / lt;  // rows beyond S: staged, never stored
-            if (!STAMP && p.lse != nullptr && h == 0 && q < S)
+            if (p.lse != nullptr && h == 0 && q < S)
                 p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -1332,7 +1254,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             if (q >= S)
                 continue;
             const float inv_l = 1.0f / lt;
-            if (!STAMP && p.lse != nullptr && h == 0)
+            if (p.lse != nullptr && h == 0)
                 p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
             unsigned char* og = o_bh + (size_t)q * p.o_rs;
 #pragma unroll
@@ -1348,27 +1270,14 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 }
         }
     }
-    if constexpr (STAMP) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the wavefront's stores have been acknowledged
-        ts[5] = wall_clock64();
-        if (lane == 0 && p.lse != nullptr && S % BM2 == 0) {  // 8 words per wavefront, 64-bit each
-            unsigned long long* rec = (unsigned long long*)(p.lse + (size_t)bh * S + (size_t)qt * BM2) + wave * 8;
-#pragma unroll
-            for (int i = 0; i < 6; ++i)
-                rec[i] = ts[i];
-            // hardware id registers: XCC_ID (hwreg 20) in the upper word, HW_ID (hwreg 4) in the lower
-            rec[6] = ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32) |
-                     (unsigned)__builtin_amdgcn_s_getreg(4 | (31 << 11));
-            rec[7] = (unsigned long long)niter;
-        }
-    }
 }
 
 // ---- host side: variant choice and launch -------------------------------------------
 
 // Kernel variants (the tile shape / wavefront count / buffering choice the paper leaves to its
 // auto-tuner, Section 4.4 and Section 7.2).  NAUT_ATTN_VARIANT=w8q32|w4q64|bm128 overrides the
-// shape-based choice for A/B runs.
+// shape-based choice for A/B runs (read at every call, so that one process can time all of them; any other
+// non-empty value makes the call fail).
 enum Variant { V_W8Q32 = 0, V_W4Q64 = 1, V_BM128 = 2 };
 constexpr const char* kVariantName[3] = {"fwd_bm256_w8q32_bn64", "fwd_bm256_w4q64_bn64", "fwd_bm128_w4q32_bn64"};
 
@@ -1381,6 +1290,8 @@ inline int pick_variant(int S, long long nbh, int D, int causal)
             return V_W4Q64;
         if (!strcmp(e, "bm128"))
             return V_BM128;
+        if (e[0] != 0)
+            return -1;  // a name that selects nothing is an error, not a silent fall-back to the rule
     }
     // Rule fitted to the timings of `python -m paper_2604_14825_amd.tune` over sequence lengths
     // 256..16384, 2..512 heads, both head dimensions, with and without the causal mask.  The
@@ -1400,6 +1311,8 @@ int launch(const Params& p, int causal, hipStream_t stream)
     const long long nbh = (long long)p.B * p.Hq;
     // The pipelined kernel exists for D <= 128; wider heads always take the 128-query kernel.
     const int variant = D > 128 ? V_BM128 : pick_variant(p.S, nbh, D, causal);
+    if (variant < 0)
+        return fail(NAUT_ERR_UNSUPPORTED, "NAUT_ATTN_VARIANT names no kernel variant (w8q32, w4q64 or bm128)");
     const long long nblocks = nbh * (variant == V_BM128 ? p.nqt : p.nqt2);
     if (nblocks > 0x7fffffffLL)
         return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");

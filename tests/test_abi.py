@@ -47,8 +47,10 @@ def test_variant_rule_and_override(monkeypatch):
     assert nb.variant_name(1, 8, 4096, 128, False, bf, bf) == small                      # too few work-groups for 256 CUs
     monkeypatch.setenv("NAUT_ATTN_VARIANT", "w4q64")
     assert nb.variant_name(1, 2, 256, 64, False, bf, bf) == "fwd_bm256_w4q64_bn64"
-    monkeypatch.setenv("NAUT_ATTN_VARIANT", "nonsense")
-    assert nb.variant_name(1, 32, 16384, 128, True, bf, bf) == big
+    monkeypatch.setenv("NAUT_ATTN_VARIANT", "nonsense")   # a name that selects nothing is reported, not ignored
+    assert nb.variant_name(1, 32, 16384, 128, True, bf, bf) is None
+    assert nb.naut_attn_fwd_raw(A, A, A, A, A, 1, 32, 32, 16384, 128, 1, 0.1, None) == nb.NAUT_ERR_UNSUPPORTED
+    assert "NAUT_ATTN_VARIANT" in nb.last_error_string()
 
 
 A = 0x10000  # a fake, 16-byte aligned, never dereferenced device address

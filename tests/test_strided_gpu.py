@@ -187,3 +187,44 @@ def test_wide_head_bshd_long_sampled_rows():
     rows = np.unique(np.concatenate([rng.integers(0, B * Hq * S, 600), [0, S - 1, B * Hq * S - 1]]))
     o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale, rows=rows)
     gu.check(o.reshape(-1, D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, "bshd D=256")
+
+
+def test_wide_head_24_heads_groups_of_two():
+    """D = 256 with B*Hq = 24: every XCD gets three heads and works on two at a time, so its last group is
+    smaller than the others (the multi-group branch of the 128-query kernel's tile scheduler)."""
+    B, Hq, Hkv, S, D, idt = 3, 8, 4, 1024, 256, synth.BF16
+    q, k, v = make(B, Hq, Hkv, S, D, idt, 9600)
+    scale = 1.0 / math.sqrt(D)
+    qd, kd, vd = (gu.to_device(a, idt) for a in (q, k, v))
+    od = torch.full((B, Hq, S, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    print("wide head, 24 heads", flush=True)
+    o, lse = run_strided(qd, kd, vd, od, True, scale)
+    assert np.isfinite(o).all(), "an output tile was never written"
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([rng.integers(0, B * Hq * S, 3000),
+                                     [bh * S + i for bh in range(B * Hq) for i in (0, 127, 128, S - 1)]]))
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale, rows=rows)
+    gu.check(o.reshape(-1, D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, "D=256, 24 heads")
+
+
+def test_wide_head_row_stride_beyond_32_bits():
+    """D = 256 with K and V rows 16 MiB apart (the largest row stride the entry point admits): S times the
+    stride passes 2^32 bytes, so the tile addresses must be formed in 64 bits."""
+    B, H, S, D, idt = 1, 1, 300, 256, synth.BF16
+    stride = 1 << 23  # elements
+    q, k, v = make(B, H, H, S, D, idt, 9700)
+    scale = 1.0 / math.sqrt(D)
+    qd = gu.to_device(q, idt)
+
+    def spread(a):
+        buf = torch.empty(S * stride, dtype=torch.bfloat16, device="cuda")  # 4.7 GiB, rows at the start of each pitch
+        rows = buf.view(S, stride)[:, :D]
+        rows.copy_(gu.to_device(a, idt)[0, 0])
+        return rows.unsqueeze(0).unsqueeze(0)  # logical [1,1,S,D]
+    kd, vd = spread(k), spread(v)
+    assert kd.stride(2) == stride and kd.stride(2) * 2 * S > 1 << 32
+    od = torch.full((B, H, S, D), float("nan"), dtype=torch.float32, device="cuda")
+    print("wide head, 16 MiB row stride", flush=True)
+    o, lse = run_strided(qd, kd, vd, od, True, scale)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale)
+    gu.check(o, lse, o_ref, lse_ref, "D=256, row stride 2^23")
