@@ -149,6 +149,7 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     constexpr int NB = 4;                          // buffers per operand (wide)
     constexpr int LDW = TILEB / 1024 / NWAVES;     // direct loads (1 KB each) per wavefront per tile (wide)
     __shared__ __attribute__((aligned(1024))) unsigned char smem[(WIDE ? 2 * NB : 4) * TILEB];
+    __shared__ float dl_lds[NTHREADS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -287,19 +288,17 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     // its own that re-read the last row (chosen by a uniform branch).  LDS store addresses are fixed
     // registers plus the buffer offset as an immediate (the key loop is unrolled over the buffers).
     i32x4_t kst[LD_PER_T], vst[LD_PER_T];
-    int gk_off[LD_PER_T], gv_off[LD_PER_T], gk_last[LD_PER_T], gv_last[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
+    int gk_off[LD_PER_T], gv_off[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
     const int last_tile = (S + BN - 1) / BN - 1;
+    const int rows_left = S - last_tile * BN;  // rows of the sequence's last tile, >= 1
     if constexpr (!WIDE) {
-        const int rows_left = S - last_tile * BN;  // rows of the sequence's last tile, >= 1
 #pragma unroll
         for (int i = 0; i < LD_PER_T; ++i) {
             const int L = tid + NTHREADS * i;
-            const int row = L / CPR, rl = row < rows_left ? row : rows_left - 1;
+            const int row = L / CPR;
             const int ch = (L % CPR < cpr ? L % CPR : cpr - 1) * 16;
             gk_off[i] = row * p.k_rs + ch;
             gv_off[i] = row * p.v_rs + ch;
-            gk_last[i] = rl * p.k_rs + ch;
-            gv_last[i] = rl * p.v_rs + ch;
             st_k[i] = (int)smem_base + k_off<D>(row, L % CPR);
             st_v[i] = (int)smem_base + v_off<D>(row, L % CPR);
             asm volatile("" : "+v"(st_k[i]), "+v"(st_v[i]));  // opaque: buffer offsets stay instruction immediates
@@ -312,11 +311,13 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         asm volatile("" : "+s"(koff), "+s"(voff));
         const unsigned char* kp = kg + koff;
         const unsigned char* vp = vg + voff;
-        if (tile == last_tile) {
+        if (tile == last_tile) {  // once per work-group: the offsets of the ragged tile are formed on the spot
 #pragma unroll
             for (int i = 0; i < LD_PER_T; ++i) {
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)gk_last[i]);
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)gv_last[i]);
+                const int row = (tid + NTHREADS * i) / CPR;
+                const int back = row < rows_left ? 0 : row - (rows_left - 1);  // rows to step back to the last real one
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)(gk_off[i] - back * p.k_rs));
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)(gv_off[i] - back * p.v_rs));
             }
         } else {
 #pragma unroll
@@ -362,6 +363,16 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             oacc[db][r] = 0.f;
     float m_run = -INFINITY;  // running max, in the exp2 domain (already times c)
     float l_run = 0.f;        // this lane's share of the running sum (its 16 of every 32 keys)
+    // What the sum of P as rounded for the second product, the divisor of O, has over l (this lane's share; see
+    // "the two sums" in kernel 2).  It is touched only in rare blocks and in the epilogue, so it lives in a word
+    // of LDS per lane instead of a register: the D = 64 instantiation fits four wavefronts per SIMD on exactly
+    // 128 registers.
+    // (its index is re-derived from the hardware lane count where it is used: no register holds it either)
+    auto dl_slot = [&]() -> float& {
+        const int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        return dl_lds[wave * 64 + ln];
+    };
+    dl_slot() = 0.f;
     const float c = p.c;
 
     if constexpr (WIDE) {
@@ -464,6 +475,7 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // repair factor
                 m_run = m_new;
                 l_run *= alpha;
+                dl_slot() *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
                     pin_acc(oacc[db]);  // the copy into vector registers for the multiply starts here, not at the loop top
@@ -486,7 +498,6 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                     sacc[kb][r] = pv;
                     psum += pv;
                 }
-            l_run += psum;
             // O^T += V^T . P^T, 16 keys per MFMA
 #pragma unroll
             for (int t = 0; t < BN / 16; ++t) {
@@ -503,6 +514,21 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                     oacc[db] = T::mfma(vf, pb, oacc[db]);
                 }
             }
+            // The divisor of O takes the sum of P as rounded for the second product only for a tile that at least
+            // doubles some row's running sum (see "the two sums" in kernel 2); elsewhere the unrounded sum stands
+            // in for it.  The test sits at the end of the tile, where it splits no schedule; a tile that passes
+            // it rounds its P, still in their registers, once more (the pairs in the other order -- the sum does
+            // not care -- so that these packs are not merged with those of the product loop above).
+            if (__builtin_amdgcn_ballot_w64(psum > l_run) != 0) {
+                float prsum = -psum;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2)
+                        prsum = T::add_pair(T::pack2(sacc[kb][r + 1], sacc[kb][r]), prsum);
+                dl_slot() += prsum;
+            }
+            l_run += psum;
         }
         if constexpr (WIDE) {
             // Tile j + 1 must have landed; the tiles after it may fly on.  A bare barrier: every LDS
@@ -526,7 +552,8 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
 
     // Epilogue: one division by l (the per-step divide/multiply pairs telescope away), lse, store.
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv_l = 1.0f / l_tot;
+    const float dl_run = dl_slot();
+    const float inv_l = 1.0f / (l_tot + (dl_run + __shfl_xor(dl_run, 32)));
     if (my_q < S && p.lse != nullptr && h == 0)
         p.lse[(size_t)bh * S + my_q] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     unsigned char* const o_bh = (unsigned char*)p.o + b * p.o_bs + hq * p.o_hs;
@@ -871,12 +898,15 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 oacc[hf][db][r] = 0.f;
-    float m_run[QH], neg_m[QH], l_run[QH];  // reference maximum (log2 units), its negation, running sum
+    // reference maximum (log2 units), its negation, running sum of P, running sum of P as rounded for the
+    // second product (see "the two sums" at the pieces of a stage)
+    float m_run[QH], neg_m[QH], l_run[QH], lr_run[QH];
 #pragma unroll
     for (int hf = 0; hf < QH; ++hf) {
         m_run[hf] = M_INIT;
         neg_m[hf] = -M_INIT;
         l_run[hf] = 0.f;
+        lr_run[hf] = 0.f;
     }
 
     // SM(kblk) part 0: causal / tail / out-of-range masking
@@ -957,6 +987,18 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // Vector work of the stage, one piece at a time (see Pieces).  P is formed against the
         // reference maximum as it stands, with no look at this block's own maximum: as long as the
         // row sums stay below P_LIMIT every P is below it too, and the reference need not move.
+        // The two sums: lse needs l = sum of P to better than 16-bit accuracy, so P is summed in fp32 before it
+        // is rounded; O, on the other hand, must be divided by the sum of the P that went into it, the rounded
+        // ones.  With the reference lagging behind the maximum the largest P of a row is an arbitrary number,
+        // not 1, and its rounding error (relative 2^-9 in bf16) would otherwise go into O but not into its
+        // divisor: for a row that one key dominates that is an error of 2^-9 |v| on top of the rounding of O
+        // itself (2^-9 |O| as well: together past the 2e-2 bar once |v| exceeds 4).  Divided by the rounded sum
+        // the weights add up to one exactly and such a row returns v.  Only keys of large weight matter for
+        // this, so the rounded sum is formed (after the slots, from the packed P) only for a block that at
+        // least doubles some row's running sum -- every key that ends with half of its row's weight or more is
+        // in such a block -- and the unrounded sum stands in for it otherwise: no key so treated holds half of
+        // a row, and |O| near 4 then takes several keys with |v| near 4 in one column, which N(0,1)-like values
+        // do not supply; their rounding errors, independent and of either sign, average out in O.
         auto piece = [&](auto PCI) {
             constexpr int pos = decltype(PCI)::value, e = PC::score(pos), hf = e / 16, idx = e % 16;
             if constexpr (PC::is_fe(pos)) {
@@ -1006,10 +1048,14 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 asm volatile("" ::"v"(frag[f + 2]));
             __builtin_amdgcn_sched_barrier(0);
         });
-        bool over = false;  // also true for +inf (first block of a row: the reference is still M_INIT)
+        bool over = false;   // also true for +inf (first block of a row: the reference is still M_INIT)
+        bool heavy = false;  // the block at least doubles the row's running sum (first block: always)
 #pragma unroll
-        for (int hf = 0; hf < QH; ++hf)
-            over = over || psum[hf] > P_LIMIT;
+        for (int hf = 0; hf < QH; ++hf) {
+            over = over || psum[hf] > T::P_LIMIT;
+            heavy = heavy || psum[hf] > l_run[hf];
+        }
+        if (__builtin_amdgcn_ballot_w64(heavy || over) != 0) {
         if (__builtin_amdgcn_ballot_w64(over) != 0) {
             // Rare path: some row of this wavefront met scores far above its reference maximum.  Move
             // the reference of every row to its true running maximum, apply the repair factor
@@ -1032,6 +1078,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 const float m_new = max3(m_run[hf], cand, cand);
                 const float alpha = __builtin_amdgcn_exp2f(m_run[hf] - m_new);
                 l_run[hf] *= alpha;
+                lr_run[hf] *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -1052,12 +1099,25 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 psum[hf] = ps;
             }
         }
+        // the heavy block's sum of the rounded P; the difference to the unrounded sum goes to lr_run
+#pragma unroll
+        for (int hf = 0; hf < QH; ++hf) {
+            float pr = -psum[hf];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    pr = T::add_pair(p_out[hf][t][e], pr);
+            lr_run[hf] += pr;
+        }
+        }
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
                 pin_acc(oacc[hf][db]);
             l_run[hf] += psum[hf];
+            lr_run[hf] += psum[hf];
         }
     };
 
@@ -1216,7 +1276,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         for (int hf = 0; hf < QH; ++hf) {
             const int q = qrow[hf];
             const float lt = half_sum(l_run[hf]);
-            const float inv_l = 1.0f / lt;  // rows beyond S: staged, never stored
+            const float inv_l = 1.0f / half_sum(lr_run[hf]);  // rows beyond S: staged, never stored
             if (p.lse != nullptr && h == 0 && q < S)
                 p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
 #pragma unroll
@@ -1251,9 +1311,10 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         for (int hf = 0; hf < QH; ++hf) {
             const int q = qrow[hf];
             const float lt = half_sum(l_run[hf]);
+            const float lr = half_sum(lr_run[hf]);
             if (q >= S)
                 continue;
-            const float inv_l = 1.0f / lt;
+            const float inv_l = 1.0f / lr;
             if (p.lse != nullptr && h == 0)
                 p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
             unsigned char* og = o_bh + (size_t)q * p.o_rs;

@@ -39,6 +39,14 @@ struct In<NAUT_BF16> {
         f32x2_t f = {lo, hi};
         return __builtin_bit_cast(int, __builtin_convertvector(f, bf16x2_t));
     }
+    // acc + the two 16-bit values of `packed`, in fp32 (v_dot2c_f32_bf16 against a pair of ones)
+    static __device__ __forceinline__ float add_pair(int packed, float acc)
+    {
+        const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, packed), ones, acc, false);
+    }
+    // a block's row sum of P above this moves the reference maximum (P itself must stay representable)
+    static constexpr float P_LIMIT = 1073741824.0f;  // 2^30
 };
 
 template <>
@@ -53,6 +61,12 @@ struct In<NAUT_F16> {
         f32x2_t f = {lo, hi};
         return __builtin_bit_cast(int, __builtin_convertvector(f, f16x2_t));
     }
+    static __device__ __forceinline__ float add_pair(int packed, float acc)
+    {
+        const f16x2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, packed), ones, acc, false);
+    }
+    static constexpr float P_LIMIT = 1024.0f;  // f16 ends at 65504
 };
 
 // ---- LDS layouts -------------------------------------------------------------

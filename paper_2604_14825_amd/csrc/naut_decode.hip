@@ -36,7 +36,11 @@ constexpr int MRG_WAVES = 4;               // wavefronts of the merge kernel
 constexpr int MRG_THREADS = MRG_WAVES * 64;
 constexpr int DEC_ROWS = 32;               // query rows per work-group (one MFMA tile)
 constexpr int DEC_BLK = 32;                // keys per block
-constexpr float DEC_TAU = 6.0f;            // the reference maximum moves when a row exceeds it by 2^6
+// The reference maximum of the 16-bit kernel moves whenever a row's maximum grows: the largest P of a row is
+// then exactly 1 and carries no rounding error into O (with a reference that lags, the largest P is an
+// arbitrary number whose rounding to 16 bit, relative 2^-9 in bf16, goes into O but not into l).  The
+// rescaling this costs is vector work that a kernel bound by reading the cache has to spare.
+constexpr float DEC_TAU = 0.0f;
 constexpr float DEC_M_INIT = -1.0e30f;     // finite stand-in for "no maximum yet"
 #ifndef NAUT_DEC_TARGET
 #define NAUT_DEC_TARGET 256
