@@ -990,15 +990,17 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // The two sums: lse needs l = sum of P to better than 16-bit accuracy, so P is summed in fp32 before it
         // is rounded; O, on the other hand, must be divided by the sum of the P that went into it, the rounded
         // ones.  With the reference lagging behind the maximum the largest P of a row is an arbitrary number,
-        // not 1, and its rounding error (relative 2^-9 in bf16) would otherwise go into O but not into its
-        // divisor: for a row that one key dominates that is an error of 2^-9 |v| on top of the rounding of O
-        // itself (2^-9 |O| as well: together past the 2e-2 bar once |v| exceeds 4).  Divided by the rounded sum
-        // the weights add up to one exactly and such a row returns v.  Only keys of large weight matter for
-        // this, so the rounded sum is formed (after the slots, from the packed P) only for a block that at
-        // least doubles some row's running sum -- every key that ends with half of its row's weight or more is
-        // in such a block -- and the unrounded sum stands in for it otherwise: no key so treated holds half of
-        // a row, and |O| near 4 then takes several keys with |v| near 4 in one column, which N(0,1)-like values
-        // do not supply; their rounding errors, independent and of either sign, average out in O.
+        // not 1, and its rounding error (up to 2^-8 relative in bf16, whose significand has 8 bits) would otherwise
+        // go into O but not into its divisor: for a row that one key dominates that is an error of up to 2^-8 |v|
+        // on top of the rounding of O itself (as much again: together past the 2e-2 bar once |v| exceeds 2.6).
+        // Divided by the rounded sum the weights add up to one exactly and such a row returns v (what is left is
+        // 2^-8 w |v - O| per key of weight w, as in any kernel that rounds P).  Only keys of large weight matter for
+        // this, so the rounded sum is formed (after the slots, from the packed P) only for a block that
+        // adds a quarter or more to some row's running sum -- every key that ends with a fifth of its row's
+        // weight or more is in such a block -- and the unrounded sum stands in for it otherwise: a key so
+        // treated adds at most 0.2 * 2^-8 |v| to the error, and |O| near 4 would take several such keys with
+        // |v| near 4 in one column, which N(0,1)-like values do not supply; the rounding errors of the many
+        // light keys, independent and of either sign, average out in O.
         auto piece = [&](auto PCI) {
             constexpr int pos = decltype(PCI)::value, e = PC::score(pos), hf = e / 16, idx = e % 16;
             if constexpr (PC::is_fe(pos)) {
@@ -1049,11 +1051,11 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             __builtin_amdgcn_sched_barrier(0);
         });
         bool over = false;   // also true for +inf (first block of a row: the reference is still M_INIT)
-        bool heavy = false;  // the block at least doubles the row's running sum (first block: always)
+        bool heavy = false;  // the block adds a quarter or more to the row's running sum (first block: always)
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf) {
             over = over || psum[hf] > T::P_LIMIT;
-            heavy = heavy || psum[hf] > l_run[hf];
+            heavy = heavy || psum[hf] > 0.25f * l_run[hf];
         }
         if (__builtin_amdgcn_ballot_w64(heavy || over) != 0) {
         if (__builtin_amdgcn_ballot_w64(over) != 0) {

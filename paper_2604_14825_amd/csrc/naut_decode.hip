@@ -38,7 +38,7 @@ constexpr int DEC_ROWS = 32;               // query rows per work-group (one MFM
 constexpr int DEC_BLK = 32;                // keys per block
 // The reference maximum of the 16-bit kernel moves whenever a row's maximum grows: the largest P of a row is
 // then exactly 1 and carries no rounding error into O (with a reference that lags, the largest P is an
-// arbitrary number whose rounding to 16 bit, relative 2^-9 in bf16, goes into O but not into l).  The
+// arbitrary number whose rounding to 16 bit, up to 2^-8 relative in bf16, goes into O but not into l).  The
 // rescaling this costs is vector work that a kernel bound by reading the cache has to spare.
 constexpr float DEC_TAU = 0.0f;
 constexpr float DEC_M_INIT = -1.0e30f;     // finite stand-in for "no maximum yet"

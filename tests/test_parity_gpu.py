@@ -90,6 +90,48 @@ def test_moving_reference_maximum(kind, variant, monkeypatch):
         gu.check(o, lse, o_ref, lse_ref, kind + "/" + variant + "/hot")
 
 
+@pytest.mark.parametrize("variant,D", [("w8q32", 128), ("w4q64", 128), ("bm128", 128), ("bm128", 64), ("bm128", 256)])
+def test_dominant_key_behind_a_lagging_reference(variant, D, monkeypatch):
+    """The last key of every fourth row (its diagonal, under the causal mask) dominates the row by a few binades --
+    too few to make a kernel move its reference maximum -- and carries values of magnitude 4 to 5.5, where one
+    bf16 step of O is 3e-2.  The largest P of such a row is an arbitrary number, not 1; unless O is divided by the sum of the
+    P that went into it, the rounding of that P (up to 2^-8) is an error of 2^-8 |v| on top of the rounding of O, and
+    the 2e-2 bar is missed."""
+    if D <= 128:
+        monkeypatch.setenv("NAUT_ATTN_VARIANT", variant)
+    B, H, S, idt, odt = 1, 4, 1500, synth.BF16, synth.BF16
+    seed = 4545 + D
+    q = synth.fill(B, H, S, D, seed, synth.TAG_Q, idt)
+    k = synth.fill(B, H, S, D, seed, synth.TAG_K, idt)
+    v = synth.fill(B, H, S, D, seed, synth.TAG_V, idt)
+    scale = 1.0 / math.sqrt(D)
+    qf, vf = _bits_to_f32(q, idt), _bits_to_f32(v, idt)
+    g = np.random.default_rng(seed)
+    # Every fourth row gets a last key of its own: key i = q_i * t_i scores `target` with row i and about
+    # target / sqrt(D) with any other row; target lies 1 to 4.5 (0.3 to 6.8 binades) above the usual maximum of
+    # a row's other scores, and that key's values have magnitude 4 to 5.5.  Everything else stays N(0,1).
+    kf = _bits_to_f32(k, idt)
+    dom = np.arange(S) % 4 == 3
+    target = (3.6 + g.uniform(1.0, 4.5, size=(B, H, S))).astype(np.float32)
+    t = target / (scale * (qf * qf).sum(-1))
+    kf[:, :, dom] = (qf * t[..., None])[:, :, dom]
+    k = synth.round16(kf, idt)
+    sign = np.where(g.random((B, H, S, D)) < 0.5, -1.0, 1.0).astype(np.float32)
+    vf[:, :, dom] = (sign * g.uniform(4.0, 5.5, size=(B, H, S, D)).astype(np.float32))[:, :, dom]
+    v = synth.round16(vf, idt)
+    print("case dominant key", variant, D, flush=True)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale)
+    assert np.abs(o_ref).max() > 4.0, "the case must reach the range where one bf16 step of O exceeds the bar"
+    # fp32 output: the kernel's own error, against the whole bar
+    o, lse = gu.run_hip(q, k, v, idt, synth.F32, True, scale)
+    gu.check(o, lse, o_ref, lse_ref, "dominant key/%s/D%d/f32 out" % (variant, D))
+    # bf16 output: the maximum only (values of magnitude 4 to 8 round to bf16 with a mean error of 8e-3 by themselves)
+    o, lse = gu.run_hip(q, k, v, idt, odt, True, scale)
+    d = np.abs(o - o_ref)
+    print("bf16 out: max|dO| %.3e mean %.3e" % (d.max(), d.mean()), flush=True)
+    assert np.isfinite(o).all() and d.max() <= gu.TOL_MAX, "dominant key/%s/D%d: max|dO| = %.3e" % (variant, D, d.max())
+
+
 @pytest.mark.parametrize("kind", ["ascending", "descending", "late_spike"])
 def test_moving_reference_maximum_wide(kind):
     """The same score profiles on the D = 256 kernel, whose rescale block moves O between register files."""
