@@ -36,6 +36,19 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitize_check(out: str, sanitize: bool = True) -> str:
+    """Compile sanitize_check.c with the oracle and the generator sources into the executable `out`
+    (under -fsanitize=address,undefined unless `sanitize` is False)."""
+    root = os.path.dirname(_HERE)
+    cmd = ["gcc", "-std=c99", "-O1", "-g", "-fopenmp", "-Wall", "-Wextra"]
+    if sanitize:
+        cmd += ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-static-libasan"]
+    cmd += [os.path.join(_HERE, "sanitize_check.c"), _SRC,
+            os.path.join(root, "paper_2604_14825_amd", "synth", "naut_synth.c"), "-o", out, "-lm"]
+    subprocess.check_call(cmd)
+    return out
+
+
 def _bind(path: str):
     """Load one compiled copy of the oracle and declare its signatures."""
     lib = ctypes.CDLL(path)

@@ -11,6 +11,8 @@ import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libnaut_attn.so")
+# the same sources built with -DNAUT_SAFE_SYNC=1 (conservative synchronisation; used by the race check only)
+LIB_SAFE_PATH = os.path.join(_HERE, "libnaut_attn_safe.so")
 
 NAUT_OK = 0
 NAUT_ERR_NULL = -1
@@ -43,6 +45,47 @@ class NautError(RuntimeError):
         self.code = code
 
 
+def load(path: str):
+    """A loaded copy of the C-ABI library at `path` with its signatures declared."""
+    L = ctypes.CDLL(path)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    L.naut_attn_fwd.restype = ci
+    L.naut_attn_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp]
+    L.naut_attn_fwd_dt.restype = ci
+    L.naut_attn_fwd_dt.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, ci, ci]
+    L.naut_last_error_string.restype = ctypes.c_char_p
+    L.naut_last_error_string.argtypes = []
+    L.naut_version.restype = ci
+    L.naut_version.argtypes = []
+    L.naut_attn_variant_name.restype = ctypes.c_char_p
+    L.naut_attn_variant_name.argtypes = [ci, ci, ci, ci, ci, ci, ci]
+    L.naut_attn_fwd_strided.restype = ci
+    L.naut_attn_fwd_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, ci, ci,
+                                        ctypes.POINTER(NautStrides)]
+    L.naut_attn_fwd_fp8.restype = ci
+    L.naut_attn_fwd_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp]
+    sz = ctypes.c_size_t
+    L.naut_attn_decode.restype = ci
+    L.naut_attn_decode.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
+    L.naut_attn_decode_dt.restype = ci
+    L.naut_attn_decode_dt.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci]
+    L.naut_attn_decode_workspace_bytes.restype = sz
+    L.naut_attn_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    L.naut_attn_fwd_fp8_strided.restype = ci
+    L.naut_attn_fwd_fp8_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp,
+                                            ctypes.POINTER(NautStrides)]
+    L.naut_attn_decode_fp8.restype = ci
+    L.naut_attn_decode_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp, sz, vp]
+    L.naut_attn_decode_strided.restype = ci
+    L.naut_attn_decode_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci,
+                                           ctypes.POINTER(NautStrides)]
+    L.naut_probe_mfma.restype = ci
+    L.naut_probe_mfma.argtypes = [vp, sz, ci, ci, ci, vp]
+    L.naut_attn_decode_static.restype = ci
+    L.naut_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp]
+    return L
+
+
 def lib():
     """The loaded C-ABI library (raises if it was never built)."""
     global _lib
@@ -51,43 +94,7 @@ def lib():
             raise RuntimeError(
                 "libnaut_attn.so is missing: build it with `python -m paper_2604_14825_amd.build` "
                 "(there is no fallback implementation)")
-        L = ctypes.CDLL(LIB_PATH)
-        vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
-        L.naut_attn_fwd.restype = ci
-        L.naut_attn_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp]
-        L.naut_attn_fwd_dt.restype = ci
-        L.naut_attn_fwd_dt.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, ci, ci]
-        L.naut_last_error_string.restype = ctypes.c_char_p
-        L.naut_last_error_string.argtypes = []
-        L.naut_version.restype = ci
-        L.naut_version.argtypes = []
-        L.naut_attn_variant_name.restype = ctypes.c_char_p
-        L.naut_attn_variant_name.argtypes = [ci, ci, ci, ci, ci, ci, ci]
-        L.naut_attn_fwd_strided.restype = ci
-        L.naut_attn_fwd_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, ci, ci,
-                                            ctypes.POINTER(NautStrides)]
-        L.naut_attn_fwd_fp8.restype = ci
-        L.naut_attn_fwd_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp]
-        sz = ctypes.c_size_t
-        L.naut_attn_decode.restype = ci
-        L.naut_attn_decode.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
-        L.naut_attn_decode_dt.restype = ci
-        L.naut_attn_decode_dt.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci]
-        L.naut_attn_decode_workspace_bytes.restype = sz
-        L.naut_attn_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
-        L.naut_attn_fwd_fp8_strided.restype = ci
-        L.naut_attn_fwd_fp8_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp,
-                                                ctypes.POINTER(NautStrides)]
-        L.naut_attn_decode_fp8.restype = ci
-        L.naut_attn_decode_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp, sz, vp]
-        L.naut_attn_decode_strided.restype = ci
-        L.naut_attn_decode_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci,
-                                               ctypes.POINTER(NautStrides)]
-        L.naut_probe_mfma.restype = ci
-        L.naut_probe_mfma.argtypes = [vp, sz, ci, ci, ci, vp]
-        L.naut_attn_decode_static.restype = ci
-        L.naut_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp]
-        _lib = L
+        _lib = load(LIB_PATH)
     return _lib
 
 

@@ -17,6 +17,9 @@ JOBS += [(os.path.join(_CSRC, "naut_attn_inst.hip"), ["-DNAUT_INST_IN=%d" % _DT[
          for i, o in (("bf16", "bf16"), ("bf16", "f32"), ("f16", "f16"), ("f16", "f32"))]
 SRCS = sorted({j[0] for j in JOBS})
 LIB = os.path.join(_HERE, "libnaut_attn.so")
+# The same sources with every hand-made synchronisation replaced by its most conservative form (-DNAUT_SAFE_SYNC=1,
+# see naut_common.h); tests/test_safe_sync_gpu.py requires the two libraries to agree bit for bit.
+LIB_SAFE = os.path.join(_HERE, "libnaut_attn_safe.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -62,6 +65,7 @@ def build_lib(extra=(), verbose=False, out=None) -> str:
 def build_all(verbose=False):
     from . import synth
     synth.build(force=True)
+    build_lib(extra=["-DNAUT_SAFE_SYNC=1"], verbose=verbose, out=LIB_SAFE)
     return build_lib(verbose=verbose)
 
 
@@ -73,4 +77,6 @@ if __name__ == "__main__":
     out = None
     if args and args[0].startswith("--out="):  # link somewhere else (A/B builds with extra -D flags)
         out, args = args[0][len("--out="):], args[1:]
+    if out is None and not args:
+        print(build_lib(extra=["-DNAUT_SAFE_SYNC=1"], verbose=True, out=LIB_SAFE))
     print(build_lib(extra=args, verbose=True, out=out))

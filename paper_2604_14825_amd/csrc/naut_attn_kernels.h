@@ -100,27 +100,27 @@ __device__ __forceinline__ void static_for(F&& f)
 template <int DT>
 struct XMfma;
 // Puts every later reader of an asm MFMA's result `d` the owed wait states behind that MFMA.
-__device__ __forceinline__ void settle(f32x16_t& d) { asm volatile("s_nop 11" : "+v"(d)); }
+__device__ __forceinline__ void settle(f32x16_t& d) { asm volatile(NAUT_NOP_SETTLE : "+v"(d)); }
 template <>
 struct XMfma<NAUT_BF16> {
     static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+        asm volatile(NAUT_NOP_SHORT "v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" NAUT_NOP_AFTER_MFMA : "=&v"(d) : "v"(a), "a"(b));
     }
     static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+        asm volatile(NAUT_NOP_SHORT "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" NAUT_NOP_AFTER_MFMA : "+v"(d) : "v"(a), "a"(b));
     }
 };
 template <>
 struct XMfma<NAUT_F16> {
     static __device__ __forceinline__ void first(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+        asm volatile(NAUT_NOP_SHORT "v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" NAUT_NOP_AFTER_MFMA : "=&v"(d) : "v"(a), "a"(b));
     }
     static __device__ __forceinline__ void acc(f32x16_t& d, i32x4_t a, i32x4_t b)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+        asm volatile(NAUT_NOP_SHORT "v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" NAUT_NOP_AFTER_MFMA : "+v"(d) : "v"(a), "a"(b));
     }
 };
 
@@ -242,8 +242,6 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             wv_col[n] = (vc < cpr ? vc : cpr - 1) * 16;
         }
     }
-    // asm, so that the compiler does not make every later LDS read wait for these loads; completion
-    // is awaited explicitly (vmcnt) before the barrier that publishes the tile.
     // The address of a load is the tile's base, a 64-bit wave-uniform pointer, plus a 32-bit lane offset inside
     // the tile (at most BN rows of the largest row stride the entry point admits); rows beyond the end of the
     // sequence re-read its last row.
@@ -257,30 +255,23 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         for (int n = 0; n < LDW; ++n) {
             const int row = wk_row[n] < last_row ? wk_row[n] : last_row;
             const int off = row * p.k_rs + wk_col[n];
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(kd + n * 1024), "v"(off), "s"(kt)
-                         : "memory", "m0");
+            load_to_lds(kd + n * 1024, off, kt);
         }
 #pragma unroll
         for (int n = 0; n < LDW; ++n) {
             const int row = wv_row[n] < last_row ? wv_row[n] : last_row;
             const int off = row * p.v_rs + wv_col[n];
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(vd + n * 1024), "v"(off), "s"(vt)
-                         : "memory", "m0");
+            load_to_lds(vd + n * 1024, off, vt);
         }
     };
     // Waits until at most `ahead` later tiles of this wavefront's loads are still in flight.
     auto wait_tiles = [&](int ahead) {
-        static_assert(2 * 2 * LDW < 64 || !WIDE, "vmcnt field");
         if (ahead >= 2)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * 2 * LDW) : "memory");
+            wait_loads<WIDE ? 2 * 2 * LDW : 0>();
         else if (ahead == 1)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LDW) : "memory");
+            wait_loads<WIDE ? 2 * LDW : 0>();
         else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wait_loads<0>();
     };
 
     // D <= 128: global -> register staging of one K and one V tile.  A load is a wave-uniform tile base
@@ -382,7 +373,7 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         for (int t = 0; t < NB - 1 && t < ntiles; ++t)
             issue_tile(t);
         wait_tiles(ntiles - 1);
-        asm volatile("s_barrier" ::: "memory");
+        tile_barrier();
     } else {
         g_load(0);
         int cpr_late = cpr;
@@ -405,6 +396,8 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             // buffer (j + NB - 1) % NB was last read in step j - 1, which every wavefront has left
             if (j + NB - 1 < ntiles)
                 issue_tile(j + NB - 1);
+            if constexpr (SAFE_SYNC)
+                tile_barrier();  // checking build: nothing in flight while the step computes
         } else if (j + 1 < ntiles)
             g_load(j + 1);
 
@@ -535,7 +528,7 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             // read of this step has been consumed by its MFMA, and the fence of __syncthreads()
             // would wait for all tile loads in flight.
             wait_tiles(ntiles - 2 - j);
-            asm volatile("s_barrier" ::: "memory");
+            tile_barrier();
         } else {
             if (j + 1 < ntiles)
                 s_store(std::integral_constant<int, U ^ 1>{});
@@ -652,7 +645,7 @@ constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no maximum yet": kee
 __device__ __forceinline__ float half_sum(float x)
 {
     float a = x, b = x;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    asm volatile(NAUT_NOP_SHORT "v_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
     return a + b;
 }
 
@@ -852,13 +845,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         }
         return t;
     };
-    // asm, so that the compiler does not make every later LDS read wait for these loads;
-    // completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
     auto issue_load = [&](const TileLoad& t, int i, const int* goff) {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :
-                     : "s"(t.dst + i * 1024), "v"(goff[i]), "s"(t.gt)
-                     : "memory", "m0");
+        load_to_lds(t.dst + i * 1024, goff[i], t.gt);
     };
     const unsigned k_lds = smem_base, v_lds = smem_base + NBUF * TILEB;
 
@@ -966,7 +954,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // s_cur was written by the asm MFMAs at the end of the previous stage: keep every vector
         // read of it 11 wait states behind them (see XMfma)
         if constexpr (!ALLV)
-            asm volatile("s_nop 11" ::: "memory");
+            asm volatile(NAUT_NOP_SETTLE ::: "memory");
         if (needs_mask(k))
             mask_block(k, s_cur);
         i32x4_t frag[NF];
@@ -1075,7 +1063,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 mx = max3(mx, s_[13], s_[14]);
                 mx = max3(mx, s_[15], s_[15]);
                 float a2 = mx, b2 = mx;
-                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
+                asm volatile(NAUT_NOP_SHORT "v_permlane32_swap_b32 %0, %1" : "+v"(a2), "+v"(b2));
                 const float cand = max3(a2, b2, b2) * c;  // -inf if the block is masked for this row
                 const float m_new = max3(m_run[hf], cand, cand);
                 const float alpha = __builtin_amdgcn_exp2f(m_run[hf] - m_new);
@@ -1206,7 +1194,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         auto side = [&](auto BLKC, auto I) {
             constexpr int BLK = decltype(BLKC)::value, i = decltype(I)::value;
             constexpr int NL = 2 * LD_PER_W, STEP = NS / NL;
-            if constexpr (BLK == 0 && STEP > 0 && i % STEP == STEP / 2 && i / STEP < NL) {
+            if constexpr (!SAFE_SYNC && BLK == 0 && STEP > 0 && i % STEP == STEP / 2 && i / STEP < NL) {
                 constexpr int q = i / STEP;
                 if constexpr (q < LD_PER_W)
                     issue_load(kt, q, k_goff);
@@ -1215,6 +1203,16 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
             }
         };
 
+        if constexpr (SAFE_SYNC) {  // checking build: the iteration's loads are issued, awaited and published first
+            tile_barrier();
+#pragma unroll
+            for (int i = 0; i < LD_PER_W; ++i)
+                issue_load(kt, i, k_goff);
+#pragma unroll
+            for (int i = 0; i < LD_PER_W; ++i)
+                issue_load(vt, i, v_goff);
+            tile_barrier();
+        }
         // stage 2j-1: Y(2j-2) with p_e, X(2j) -> s_e, SM(2j-1): s_o -> p_o
         stage(std::integral_constant<int, 0>{}, UC, 2 * j - 1, carry, s_o, s_e, p_e, p_o,
               [&](auto I) { side(std::integral_constant<int, 0>{}, I); });
@@ -1225,13 +1223,13 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
         // The last slots of the next iteration already read the tiles of the one after it, so the
         // tiles issued LA-2 iterations ago must have landed by now; newer ones may fly on.
         static_assert(LA >= 2 && (LA - 2) * 2 * LD_PER_W < 64, "vmcnt field");
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
+        wait_loads<(LA - 2) * 2 * LD_PER_W>();
         // A bare barrier, not __syncthreads(): the fence in the latter would first drain the LDS
         // reads in flight, which are this wavefront's prefetch for the next stage.  They target
         // tiles published by the previous barrier and buffers that no load overwrites before the
         // barrier after this one, so they may stay in flight; the tile loads to be published have
         // been awaited just above.
-        asm volatile("s_barrier" ::: "memory");
+        tile_barrier();
     };
     for (int j0 = 0; j0 < n_act; j0 += NBUF) {
         static_for<0, NBUF>([&](auto UC) {
@@ -1243,14 +1241,18 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
     for (int j = n_act; j < niter; ++j) {  // this wavefront's part of the remaining tiles, one barrier each
         const TileLoad kt = tile_load(kg, p.k_rs, k_lds, j + LA, (j + LA) % NBUF, k_goff, k_goff_last);
         const TileLoad vt = tile_load(vg, p.v_rs, v_lds, j + LA - 1, (j + LA - 1) % NBUF, v_goff, v_goff_last);
+        if constexpr (SAFE_SYNC)
+            tile_barrier();  // checking build: the same three barriers per iteration as the wavefronts still computing
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i)
             issue_load(kt, i, k_goff);
 #pragma unroll
         for (int i = 0; i < LD_PER_W; ++i)
             issue_load(vt, i, v_goff);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((LA - 2) * 2 * LD_PER_W) : "memory");
-        asm volatile("s_barrier" ::: "memory");
+        if constexpr (SAFE_SYNC)
+            tile_barrier();
+        wait_loads<(LA - 2) * 2 * LD_PER_W>();
+        tile_barrier();
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 

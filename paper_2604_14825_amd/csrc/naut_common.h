@@ -22,6 +22,61 @@ typedef short i16x4_t __attribute__((ext_vector_type(4)));
 
 #define NAUT_LDS __attribute__((address_space(3)))
 
+// ---- hand-made synchronisation, and the build that checks it -----------------------------------------
+// The kernels publish direct-to-LDS tile loads with bare s_barrier instructions, count their own loads in
+// flight (s_waitcnt vmcnt(n)) and owe a few wait states around instructions written as asm.  A library built
+// with -DNAUT_SAFE_SYNC=1 replaces all of that by the most conservative form: every such barrier first waits
+// for every memory operation of the wavefront and is a full __syncthreads(); every counted wait is a wait for
+// all loads; tile loads are issued, awaited and published before the step that issued them computes anything
+// (nothing is in flight during compute: single-stage); and every owed wait state is paid several times over.
+// The arithmetic and its order are the same, so the two builds must agree bit for bit; a difference is a race
+// or a missing wait in the fast build (tests/test_safe_sync_gpu.py compares them).
+#ifndef NAUT_SAFE_SYNC
+#define NAUT_SAFE_SYNC 0
+#endif
+constexpr bool SAFE_SYNC = NAUT_SAFE_SYNC != 0;
+#if NAUT_SAFE_SYNC
+#define NAUT_NOP_SHORT "s_nop 7\n\t"                         /* in place of the 1 or 2 wait states owed */
+#define NAUT_NOP_AFTER_MFMA "\n\ts_nop 15\n\ts_nop 15"         /* 32 wait states behind every asm MFMA */
+#define NAUT_NOP_SETTLE "s_nop 15\n\ts_nop 15"
+#else
+#define NAUT_NOP_SHORT "s_nop 1\n\t"
+#define NAUT_NOP_AFTER_MFMA ""
+#define NAUT_NOP_SETTLE "s_nop 11"
+#endif
+
+// The barrier that publishes tile loads (the loads to be published have been awaited by their wavefronts).
+__device__ __forceinline__ void tile_barrier()
+{
+    if constexpr (SAFE_SYNC) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+    } else {
+        asm volatile("s_barrier" ::: "memory");
+    }
+}
+// Waits until at most N of this wavefront's vector memory operations are still in flight.
+template <int N>
+__device__ __forceinline__ void wait_loads()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt field");
+    if constexpr (SAFE_SYNC)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// One 1 KB direct global->LDS load: lane i's 16 bytes from `base` + `off` land at LDS address `dst` + 16 i.
+// asm, so that the compiler does not make every later LDS read wait for these loads; their completion is
+// awaited explicitly (wait_loads) before the barrier that publishes the tile.
+__device__ __forceinline__ void load_to_lds(unsigned dst, int off, const unsigned char* base)
+{
+#if NAUT_SAFE_SYNC
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 7\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(off), "s"(base) : "memory", "m0");
+#else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(off), "s"(base) : "memory", "m0");
+#endif
+}
+
 // ---- per-dtype pieces ------------------------------------------------------
 
 template <int DT>
@@ -129,7 +184,7 @@ __device__ __forceinline__ i32x4_t load_vt_frag(const unsigned char* vt, int kba
 __device__ __forceinline__ float half_max(float x)
 {
     float a = x, b = x;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    asm volatile(NAUT_NOP_SHORT "v_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
     return fmaxf(a, b);
 }
 

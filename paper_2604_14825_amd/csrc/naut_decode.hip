@@ -74,7 +74,7 @@ struct DecodeParams {
 __device__ __forceinline__ float half_sum_f(float x)
 {
     float a = x, b = x;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    asm volatile(NAUT_NOP_SHORT "v_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
     return a + b;
 }
 
@@ -248,14 +248,8 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
                 vr = vr < rows_left ? vr : rows_left - 1;
             }
             const int ko = kr * p.k_rs + k_col[n], vo = vr * p.v_rs + v_col[n];
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst + n * 1024), "v"(ko), "s"(kp)
-                         : "memory", "m0");
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst + BLKB + n * 1024), "v"(vo), "s"(vp)
-                         : "memory", "m0");
+            load_to_lds(dst + n * 1024, ko, kp);
+            load_to_lds(dst + BLKB + n * 1024, vo, vp);
         }
     };
 
@@ -277,7 +271,7 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
         const bool more = blk + DEC_WAVES < blk_end;
         if (more) {
             issue(blk + DEC_WAVES, buf ^ 1);
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NLD) : "memory");
+            wait_loads<2 * NLD>();
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
@@ -427,14 +421,8 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
                 vr = vr < rows_left ? vr : rows_left - 1;
             }
             const int ko = kr * D + k_col[n], vo = vr * D + v_col[n];
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst + n * 1024), "v"(ko), "s"(kp)
-                         : "memory", "m0");
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst + BLKB + n * 1024), "v"(vo), "s"(vp)
-                         : "memory", "m0");
+            load_to_lds(dst + n * 1024, ko, kp);
+            load_to_lds(dst + BLKB + n * 1024, vo, vp);
         }
     };
 
@@ -463,7 +451,7 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
         const bool more = blk + DEC_WAVES < blk_end;
         if (more) {
             issue(blk + DEC_WAVES, buf ^ 1);
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NLD) : "memory");
+            wait_loads<2 * NLD>();
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
