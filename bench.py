@@ -409,8 +409,10 @@ def main() -> int:
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 5}))
         return 0
     if args.calibrate_mfma:
-        res = mfma_ceiling(nb, torch, ncu)
-        res["published_peak_tflops"] = PEAK_BF16_TFLOPS
+        # on every compute unit, and on half of them: the second shows what one compute unit sustains when the
+        # chip's power budget is shared by fewer of them
+        res = {"all_compute_units": mfma_ceiling(nb, torch, ncu), "half_the_compute_units": mfma_ceiling(nb, torch, ncu // 2),
+               "published_peak_tflops": PEAK_BF16_TFLOPS, "compute_units": ncu}
         print(json.dumps({"calibrate_mfma": res}))
         return 0
 
