@@ -1362,12 +1362,16 @@ inline int pick_variant(int S, long long nbh, int D, int causal)
     // 256..16384, 2..512 heads, both head dimensions, with and without the causal mask.  The
     // pipelined 256-query kernel halves the K/V traffic per FLOP but pays a fill and a drain stage
     // per work-group and needs a full wave of work-groups: it wins once there is one work-group per
-    // CU and the key loop is long enough (average keys per query: 512 and up at D = 128, above 1024
-    // at D = 64).  The 64-queries-per-wavefront variant was never the fastest and is selectable by
-    // name only.
+    // CU and the key loop is long enough.  At D = 128 that is an average of 512 keys per query
+    // without the mask and 1024 with it (the 128-query tiles follow the causal diagonal more
+    // closely); at D = 64, where the softmax and not the MFMAs sets the pace and the 128-query
+    // kernel keeps three wavefronts per SIMD, only from 8192 keys per query.  The
+    // 64-queries-per-wavefront variant is within 2 % of the fastest where it wins at all and is
+    // selectable by name only.
     const long long wg256 = nbh * ((S + BM2 - 1) / BM2);
-    const long long loop_work = (long long)(causal ? (S + 1) / 2 : S) * D;
-    return (wg256 >= 256 && loop_work >= (D > 64 ? 65536 : 65537)) ? V_W8Q32 : V_BM128;
+    const int avg_keys = causal ? (S + 1) / 2 : S;
+    const int min_keys = D > 64 ? (causal ? 1024 : 512) : 8192;
+    return (wg256 >= 256 && avg_keys >= min_keys) ? V_W8Q32 : V_BM128;
 }
 
 template <int D, int DT_IN, int DT_OUT>

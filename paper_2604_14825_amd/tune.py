@@ -7,7 +7,9 @@ ships three compiled variants and a fixed rule that chooses among them from the 
 is the measurement behind that rule: it runs each variant through the C ABI (selected with the
 NAUT_ATTN_VARIANT environment variable, which the library reads at every call), prints one line per
 shape with the time of each variant, the fastest one and the one the built-in rule picks, and
-flags disagreements.  Inputs are random (timing only; parity is the test-suite's job).
+flags disagreements.  Inputs come from the seeded generator of the benchmark workloads (N(0,1) rounded to
+bf16; timing only, parity is the test-suite's job); the variants take turns launch by launch and the time of
+a variant is the median over its launches.
 
     python -m paper_2604_14825_amd.tune            # default grid
     python -m paper_2604_14825_amd.tune --shapes 1,32,32,16384,128,1  # B,Hq,Hkv,S,D,causal
@@ -44,6 +46,7 @@ def main() -> int:
     ap.add_argument("--json", default=None, help="also write the table to this file")
     args = ap.parse_args()
 
+    import numpy as np
     import torch
     from . import binding as nb
     from . import synth
@@ -57,28 +60,35 @@ def main() -> int:
     rows = []
     print("%-34s %s   best      rule" % ("B,Hq,Hkv,S,D,causal", " ".join("%9s" % v for v in VARIANTS)))
     for (B, Hq, Hkv, S, D, causal) in shapes:
-        g = torch.Generator(device="cuda").manual_seed(1234)
-        q = torch.randn((B, Hq, S, D), generator=g, device="cuda").to(torch.bfloat16)
-        k = torch.randn((B, Hkv, S, D), generator=g, device="cuda").to(torch.bfloat16)
-        v = torch.randn((B, Hkv, S, D), generator=g, device="cuda").to(torch.bfloat16)
+        seed = synth.BASE_SEED + 5000
+        q, k, v = (torch.from_numpy(synth.fill(B, H, S, D, seed, tag, synth.BF16).view(np.int16)).cuda().view(torch.bfloat16)
+                   for H, tag in ((Hq, synth.TAG_Q), (Hkv, synth.TAG_K), (Hkv, synth.TAG_V)))
         o = torch.empty_like(q)
         lse = torch.empty((B, Hq, S), dtype=torch.float32, device="cuda")
         scale = D ** -0.5
         os.environ.pop("NAUT_ATTN_VARIANT", None)
         rule = nb.variant_name(B, Hq, S, D, bool(causal), synth.BF16, synth.BF16)
-        times = {}
-        for var in VARIANTS:
+        def run(var):
             os.environ["NAUT_ATTN_VARIANT"] = var
+            nb.naut_attn_fwd(q, k, v, o, lse, bool(causal), scale, stream=stream)
+
+        for var in VARIANTS:
             for _ in range(3):
-                nb.naut_attn_fwd(q, k, v, o, lse, bool(causal), scale, stream=stream)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record(stream)
-            for _ in range(args.reps):
-                nb.naut_attn_fwd(q, k, v, o, lse, bool(causal), scale, stream=stream)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            times[var] = e0.elapsed_time(e1) / args.reps * 1e3  # microseconds
+                run(var)
+        # the variants take turns launch by launch, so that a drift of the clock during the measurement
+        # falls on all of them alike
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * len(VARIANTS))] for _ in range(args.reps)]
+        torch.cuda.synchronize()
+        for r in range(args.reps):
+            for i, var in enumerate(VARIANTS):
+                ev[r][2 * i].record(stream)
+                run(var)
+                ev[r][2 * i + 1].record(stream)
+        torch.cuda.synchronize()
+        times = {}
+        for i, var in enumerate(VARIANTS):
+            per = sorted(ev[r][2 * i].elapsed_time(ev[r][2 * i + 1]) for r in range(args.reps))
+            times[var] = per[len(per) // 2] * 1e3  # microseconds, median
         os.environ.pop("NAUT_ATTN_VARIANT", None)
         best = min(times, key=times.get)
         rule_short = [s for s, l in LONG_NAME.items() if l == rule][0]
