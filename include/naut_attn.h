@@ -112,7 +112,8 @@ int naut_attn_fwd_strided(const void* q, const void* k, const void* v, void* o, 
  * tensors are descale_q * q, descale_k * k, descale_v * v (all descale factors > 0).  o is bf16, lse fp32.
  * Both products run on the FP8 matrix instructions with fp32 accumulation; P is rounded to E4M3 for the
  * second product (that rounding, relative 2^-4, is what the accuracy of this entry point is bound by).
- * D is 64 or 128.  Everything else as naut_attn_fwd.
+ * D is a multiple of 16, at most 128 (a head narrower than 64 or 128 runs on the next wider kernel: the
+ * missing columns of Q read as zero and those of O are not stored).  Everything else as naut_attn_fwd.
  */
 int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse,
                       int B, int Hq, int Hkv, int S, int D, int causal, float scale,
@@ -121,8 +122,8 @@ int naut_attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, floa
 /*
  * The same on strided tensors (e.g. sequence-major [B][S][H][D], the layout FP8 attention is usually fed):
  * `st` as in naut_attn_fwd_strided, in elements, except that q/k/v strides must be multiples of 16 (their
- * elements are bytes and rows are read 16 bytes at a time); o is bf16, its strides multiples of 4.  D is 64 or
- * 128.  st = NULL means contiguous, which is what naut_attn_fwd_fp8 passes.
+ * elements are bytes and rows are read 16 bytes at a time); o is bf16, its strides multiples of 4.  D as in
+ * naut_attn_fwd_fp8.  st = NULL means contiguous, which is what naut_attn_fwd_fp8 passes.
  */
 int naut_attn_fwd_fp8_strided(const void* q, const void* k, const void* v, void* o, float* lse,
                               int B, int Hq, int Hkv, int S, int D, int causal, float scale,
@@ -178,8 +179,8 @@ int naut_attn_decode_dt(const void* q, const void* k, const void* v, void* o, fl
  * sequence-major K/V cache [B][Sk][Hkv][D] has {Sk*Hkv*D, D, Hkv*D}.  Same rules as naut_attn_fwd_strided
  * (q/k/v strides non-negative multiples of 8, o strides positive multiples of 4, sequence strides between D
  * and 2^23); st = NULL means contiguous, which is what naut_attn_decode_dt passes.  lse stays dense.
- * D may be any multiple of 8 up to 128 here (a narrower head runs on the 64- or 128-wide kernel, as in
- * naut_attn_fwd_strided); naut_attn_decode and naut_attn_decode_dt keep D = 64 or 128.
+ * D may be any multiple of 8 up to 256 here (a head narrower than 64, 128 or 256 runs on the next wider
+ * kernel, as in naut_attn_fwd_strided); naut_attn_decode and naut_attn_decode_dt keep D = 64 or 128.
  */
 int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* o, float* lse,
                              int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
@@ -196,6 +197,17 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
                          int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
                          float descale_q, float descale_k, float descale_v,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same on strided tensors, e.g. a sequence-major FP8 cache [B][Sk][Hkv][D]: `st` as in
+ * naut_attn_decode_strided, in elements, with the FP8 rules of naut_attn_fwd_fp8_strided (q/k/v strides
+ * multiples of 16, o strides multiples of 4, sequence strides between D and 2^23).  D may be any multiple
+ * of 16 up to 128 here.  st = NULL means contiguous, which is what naut_attn_decode_fp8 passes.
+ */
+int naut_attn_decode_fp8_strided(const void* q, const void* k, const void* v, void* o, float* lse,
+                                 int B, int Hq, int Hkv, int Sq, int Sk, int D, int causal, float scale,
+                                 float descale_q, float descale_k, float descale_v,
+                                 void* workspace, size_t workspace_bytes, void* stream, const naut_strides* st);
 
 /*
  * naut_attn_decode for callers that cannot allocate or pass a workspace: code recorded under HIP graph

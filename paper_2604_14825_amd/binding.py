@@ -27,7 +27,7 @@ NAUT_F32 = 2
 
 EXPORTS = ("naut_attn_fwd", "naut_attn_fwd_dt", "naut_last_error_string", "naut_version",
            "naut_attn_variant_name", "naut_attn_decode", "naut_attn_decode_dt", "naut_attn_decode_workspace_bytes",
-           "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided", "naut_attn_fwd_fp8_strided", "naut_attn_decode_fp8",
+           "naut_attn_fwd_strided", "naut_attn_fwd_fp8", "naut_attn_decode_strided", "naut_attn_fwd_fp8_strided", "naut_attn_decode_fp8", "naut_attn_decode_fp8_strided",
            "naut_attn_decode_static", "naut_probe_mfma")
 
 
@@ -76,6 +76,9 @@ def load(path: str):
                                             ctypes.POINTER(NautStrides)]
     L.naut_attn_decode_fp8.restype = ci
     L.naut_attn_decode_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp, sz, vp]
+    L.naut_attn_decode_fp8_strided.restype = ci
+    L.naut_attn_decode_fp8_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, cf, cf, cf, vp, sz, vp,
+                                               ctypes.POINTER(NautStrides)]
     L.naut_attn_decode_strided.restype = ci
     L.naut_attn_decode_strided.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp, ci, ci,
                                            ctypes.POINTER(NautStrides)]
@@ -426,6 +429,50 @@ def naut_attn_decode_fp8(q, k, v, o, lse, causal: bool, scale: float, descale_q:
     rc = naut_attn_decode_fp8_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv, Sq, Sk, D,
                                   causal, scale, descale_q, descale_k, descale_v, workspace.data_ptr(),
                                   workspace.numel() * workspace.element_size(), stream.cuda_stream)
+    if rc != NAUT_OK:
+        raise NautError(rc, last_error_string())
+
+
+def naut_attn_decode_fp8_strided_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D, causal, scale, dq, dk,
+                                     dv, ws_ptr, ws_bytes, stream_ptr, strides) -> int:
+    """Direct call with integer device addresses; `strides` is a NautStrides, a 12-tuple or None."""
+    if strides is not None and not isinstance(strides, NautStrides):
+        strides = NautStrides(*[int(x) for x in strides])
+    ref = ctypes.byref(strides) if strides is not None else None
+    return int(lib().naut_attn_decode_fp8_strided(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, Hq, Hkv, Sq, Sk, D,
+                                                  int(causal), float(scale), float(dq), float(dk), float(dv), ws_ptr,
+                                                  ws_bytes, stream_ptr, ref))
+
+
+def naut_attn_decode_fp8_strided(q, k, v, o, lse, causal: bool, scale: float, descale_q: float, descale_k: float,
+                                 descale_v: float, workspace, stream=None):
+    """FP8 decode-time attention on torch device tensors indexed q,o [B,Hq,Sq,D] and k,v [B,Hkv,Sk,D] with arbitrary
+    batch/head/sequence strides (the D axis contiguous): q,k,v 1-byte tensors (E4M3), o bf16; lse contiguous fp32
+    [B,Hq,Sq] or None; workspace contiguous, as for naut_attn_decode."""
+    import torch
+    for t in (q, k, v, o):
+        if not (t.is_cuda and t.dim() == 4 and t.stride(3) == 1):
+            raise ValueError("q, k, v, o must be 4-d device tensors with a contiguous last axis")
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous device tensor")
+    if any(t.element_size() != 1 for t in (q, k, v)) or o.dtype != torch.bfloat16:
+        raise ValueError("q, k, v must be 1-byte tensors (E4M3) and o bf16")
+    B, Hq, Sq, D = q.shape
+    Hkv, Sk = k.shape[1], k.shape[2]
+    if tuple(k.shape) != (B, Hkv, Sk, D) or tuple(v.shape) != (B, Hkv, Sk, D) or tuple(o.shape) != (B, Hq, Sq, D):
+        raise ValueError("shape mismatch between q, k, v, o")
+    lse_ptr = None
+    if lse is not None:
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, Hq, Sq)):
+            raise ValueError("lse must be a contiguous fp32 device tensor [B,Hq,Sq]")
+        lse_ptr = lse.data_ptr()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    st = NautStrides(*[t.stride(a) for t in (q, k, v, o) for a in (0, 1, 2)])
+    rc = naut_attn_decode_fp8_strided_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse_ptr, B, Hq, Hkv,
+                                          Sq, Sk, D, causal, scale, descale_q, descale_k, descale_v,
+                                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          stream.cuda_stream, st)
     if rc != NAUT_OK:
         raise NautError(rc, last_error_string())
 

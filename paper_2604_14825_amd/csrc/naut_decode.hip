@@ -81,7 +81,7 @@ __device__ __forceinline__ float half_sum_f(float x)
 // Tail of a split kernel: the four wavefronts' partial (O, m, l) are merged through LDS (each wavefront
 // reuses its own, now idle, region of REGION bytes) and the work-group's partial goes to the workspace.
 // m is the reference maximum the wavefront's l and O are relative to (log2 units).
-template <int D, int REGION>
+template <int D, int REGION, int NW>
 __device__ __forceinline__ void merge_wavefronts(unsigned char* smem, const f32x16_t (&oacc)[D / 32], float m_run,
                                                  float l_run, const DecodeParams& p, int bhk, int chunk, int split)
 {
@@ -112,15 +112,17 @@ __device__ __forceinline__ void merge_wavefronts(unsigned char* smem, const f32x
     }
     __syncthreads();
 
-    // thread -> (row, D/8 consecutive d); partial written to the workspace
-    if (tid >= DEC_ROWS * 8)
-        return;
-    constexpr int DPT = D / 8;  // floats per thread: 16 (D = 128) or 8 (D = 64)
-    const int r_out = tid >> 3, d0 = (tid & 7) * DPT;
-    float mw[DEC_WAVES], lw[DEC_WAVES];
+    // (row, D/8 consecutive d) items, dealt to the threads; partial written to the workspace
+    constexpr int DPT = D / 8;  // floats per item: 32 (D = 256), 16 (D = 128) or 8 (D = 64)
+    const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
+    const size_t part = ((size_t)bhk * p.nchunks + chunk) * p.nsplit + split;
+#pragma unroll
+    for (int item = tid; item < DEC_ROWS * 8; item += NW * 64) {
+    const int r_out = item >> 3, d0 = (item & 7) * DPT;
+    float mw[NW], lw[NW];
     float M = DEC_M_INIT;
 #pragma unroll
-    for (int w = 0; w < DEC_WAVES; ++w) {
+    for (int w = 0; w < NW; ++w) {
         const float* ml = (const float*)(smem + w * REGION) + DEC_ROWS * OSTRIDE;
         mw[w] = ml[r_out];
         lw[w] = ml[DEC_ROWS + r_out];
@@ -132,7 +134,7 @@ __device__ __forceinline__ void merge_wavefronts(unsigned char* smem, const f32x
     for (int i = 0; i < DPT / 4; ++i)
         acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int w = 0; w < DEC_WAVES; ++w) {
+    for (int w = 0; w < NW; ++w) {
         const float f = __builtin_amdgcn_exp2f(mw[w] - M);
         L += f * lw[w];
         const float* ow = (const float*)(smem + w * REGION) + r_out * OSTRIDE + d0;
@@ -142,33 +144,36 @@ __device__ __forceinline__ void merge_wavefronts(unsigned char* smem, const f32x
             acc[i] += x * f;
         }
     }
-    const size_t nparts = (size_t)p.B * p.Hkv * p.nchunks * p.nsplit;
-    const size_t part = ((size_t)bhk * p.nchunks + chunk) * p.nsplit + split;
     if (chunk * DEC_ROWS + r_out >= p.R)
-        return;  // rows past the last one are padding: nobody reads their partials
+        continue;  // rows past the last one are padding: nobody reads their partials
     float* ws_o = p.ws + (part * DEC_ROWS + r_out) * D + d0;
 #pragma unroll
     for (int i = 0; i < DPT / 4; ++i)
         *(f32x4_t*)(ws_o + 4 * i) = acc[i];
-    if ((tid & 7) == 0) {
+    if ((item & 7) == 0) {
         float* ws_m = p.ws + nparts * DEC_ROWS * D;
         float* ws_l = ws_m + nparts * DEC_ROWS;
         ws_m[part * DEC_ROWS + r_out] = M;
         ws_l[part * DEC_ROWS + r_out] = L;
     }
+    }
 }
 
+// wavefronts of the 16-bit split kernel: the four LDS blocks of a wavefront are 64 KB at D = 256
+constexpr int dec_waves(int D) { return D > 128 ? 2 : DEC_WAVES; }
+
 template <int D, int DT_IN>
-__global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const DecodeParams p)
+__global__ __launch_bounds__(dec_waves(D) * 64, 1) void naut_decode_split_kernel(const DecodeParams p)
 {
     using T = In<DT_IN>;
+    constexpr int NW = dec_waves(D);
     constexpr int ROWB = D * 2;
     constexpr int BLKB = DEC_BLK * ROWB;   // one 32-key block of K or V
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
     constexpr int NLD = BLKB / 1024;       // direct loads (1 KB each) per block and operand
 
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[DEC_WAVES * 4 * BLKB];  // per wavefront: K0 V0 K1 V1
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NW * 4 * BLKB];  // per wavefront: K0 V0 K1 V1
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -211,13 +216,14 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
         const int P = n * 64 + lane;
         {
             const int line = P >> 4, pos = P & 15;
-            const int off = ((line << 4) + (pos ^ (line & 15))) * 16;  // byte offset in a dense [32][D] block
+            const int key = D > 128 ? line >> 1 : line;                // the inverse of k_off
+            const int off = ((line << 4) + (pos ^ (key & 15))) * 16;   // byte offset in a dense [32][D] block
             k_row[n] = off / ROWB;
             const int kc = off % ROWB / 16;
             k_col[n] = (kc < p.cpr ? kc : p.cpr - 1) * 16;
         }
-        if constexpr (D == 128) {
-            const int r = P >> 4, cc = P & 15;
+        if constexpr (D >= 128) {
+            const int r = P / (D / 8), cc = P % (D / 8);
             const int vc = cc ^ ((r & 3) << 2);
             v_row[n] = r;
             v_col[n] = (vc < p.cpr ? vc : p.cpr - 1) * 16;
@@ -262,15 +268,16 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
     float m_run = DEC_M_INIT;  // reference maximum, log2 units (already times c)
     float l_run = 0.f;         // this lane's share of the running sum (its 16 of every 32 keys)
 
-    // This wavefront's blocks: blk_begin + wave, + 4, ...  Block n+1 is in flight while block n is used.
+    // This wavefront's blocks: blk_begin + wave, + NW, ...  Block n+1 is in flight while block n is used.
+    static_assert(2 * NLD < 64, "vmcnt field");
     int blk = blk_begin + wave;
     if (blk < blk_end)
         issue(blk, 0);
-    for (int it = 0; blk < blk_end; blk += DEC_WAVES, ++it) {
+    for (int it = 0; blk < blk_end; blk += NW, ++it) {
         const int buf = it & 1;
-        const bool more = blk + DEC_WAVES < blk_end;
+        const bool more = blk + NW < blk_end;
         if (more) {
-            issue(blk + DEC_WAVES, buf ^ 1);
+            issue(blk + NW, buf ^ 1);
             wait_loads<2 * NLD>();
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -332,12 +339,13 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_kernel(const
         }
     }
 
-    merge_wavefronts<D, 4 * BLKB>(smem, oacc, m_run, l_run, p, bhk, chunk, split);
+    merge_wavefronts<D, 4 * BLKB, NW>(smem, oacc, m_run, l_run, p, bhk, chunk, split);
 }
 
-// The same split kernel on FP8 (E4M3) Q, K and V, contiguous tensors: 64-key blocks (one 32x32x64 MFMA
-// covers 64 keys of P.V), the LDS layouts, transposed byte reads and the 2^7 scaling of P of the FP8
-// prefill kernel, the blocks dealt to the wavefronts and double-buffered in LDS exactly as above.
+// The same split kernel on FP8 (E4M3) Q, K and V: 64-key blocks (one 32x32x64 MFMA covers 64 keys of
+// P.V), the LDS layouts, transposed byte reads and the 2^7 scaling of P of the FP8 prefill kernel, the
+// blocks dealt to the wavefronts and double-buffered in LDS exactly as above; strides and narrower heads
+// as above too, in 16-byte chunks of 16 values (p.cpr counts 8 values: two per chunk here).
 // bps counts 64-key blocks here.  The partial's reference maximum is stored as m - 7, which makes its l
 // and O (both carry the factor 2^7) relative to it in the plain sense the merge kernel expects.
 constexpr int DEC8_BLK = 64;
@@ -367,10 +375,11 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
     const int Sk = p.Sk;
     const float c = p.c;
 
-    // contiguous tensors: the R rows of this (batch, K/V head) follow each other in q
-    const unsigned char* qg = (const unsigned char*)p.q + (size_t)(b * p.Hq + hk * g) * p.Sq * D;
-    const unsigned char* kg = (const unsigned char*)p.k + (size_t)bhk * Sk * D;
-    const unsigned char* vg = (const unsigned char*)p.v + (size_t)bhk * Sk * D;
+    // The R rows of this (batch, K/V head): row r is position r % Sq of query head hk*g + r / Sq.
+    const unsigned char* qg = (const unsigned char*)p.q + b * p.q_bs + (long long)(hk * g) * p.q_hs;
+    const unsigned char* kg = (const unsigned char*)p.k + b * p.k_bs + hk * p.k_hs;
+    const unsigned char* vg = (const unsigned char*)p.v + b * p.v_bs + hk * p.v_hs;
+    const int cpr16 = p.cpr >> 1;  // real 16-byte chunks per row
 
     const int row = chunk * DEC_ROWS + l32;                 // the query row this lane owns
     const int row_ld = row < p.R ? row : p.R - 1;
@@ -380,8 +389,10 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
     i32x8_t qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        const i32x4_t lo = *(const i32x4_t*)(qg + (size_t)row_ld * D + ks * 64 + h * 32);
-        const i32x4_t hi = *(const i32x4_t*)(qg + (size_t)row_ld * D + ks * 64 + h * 32 + 16);
+        const unsigned char* qrow = qg + (row_ld / p.Sq) * p.q_hs + (long long)(row_ld % p.Sq) * p.q_rs;
+        const int c0 = ks * 4 + h * 2;  // this lane's two 16-byte chunks of the row
+        const i32x4_t lo = c0 < cpr16 ? *(const i32x4_t*)(qrow + c0 * 16) : i32x4_t{0, 0, 0, 0};
+        const i32x4_t hi = c0 + 1 < cpr16 ? *(const i32x4_t*)(qrow + c0 * 16 + 16) : i32x4_t{0, 0, 0, 0};
         qf[ks] = i32x8_t{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     }
 #pragma unroll
@@ -396,10 +407,12 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
         const int P = n * 64 + lane;
         const int r = P / CPR, pc = P % CPR;
         k_row[n] = r;
-        k_col[n] = (pc ^ ((r >> 1) & (CPR - 1))) * 16;
+        const int kc = pc ^ ((r >> 1) & (CPR - 1));  // logical chunk that k8_off places at position pc
+        k_col[n] = (kc < cpr16 ? kc : cpr16 - 1) * 16;
         const int key = D == 128 ? (((r >> 1) & 1) | (((r >> 3) & 1) << 1)) : ((r >> 3) & 1);
         v_row[n] = r;
-        v_col[n] = (((pc >> 1) ^ key) << 5) + (pc & 1) * 16;
+        const int vc = (((pc >> 1) ^ key) << 1) + (pc & 1);  // likewise for v8_off (32-byte chunks, two halves)
+        v_col[n] = (vc < cpr16 ? vc : cpr16 - 1) * 16;
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem + (unsigned)(wave * 4 * BLKB);
     unsigned char* my_lds = smem + wave * 4 * BLKB;
@@ -409,8 +422,8 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
     const int blk_end = blk_begin + p.bps < nblk ? blk_begin + p.bps : nblk;
 
     auto issue = [&](int blk, int buf) {
-        const unsigned char* kp = kg + (size_t)blk * BLKB;
-        const unsigned char* vp = vg + (size_t)blk * BLKB;
+        const unsigned char* kp = kg + (size_t)blk * DEC8_BLK * p.k_rs;
+        const unsigned char* vp = vg + (size_t)blk * DEC8_BLK * p.v_rs;
         const int rows_left = Sk - blk * DEC8_BLK;  // >= 1
         const unsigned dst = lds0 + (unsigned)(buf * 2 * BLKB);
 #pragma unroll
@@ -420,7 +433,7 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
                 kr = kr < rows_left ? kr : rows_left - 1;
                 vr = vr < rows_left ? vr : rows_left - 1;
             }
-            const int ko = kr * D + k_col[n], vo = vr * D + v_col[n];
+            const int ko = kr * p.k_rs + k_col[n], vo = vr * p.v_rs + v_col[n];
             load_to_lds(dst + n * 1024, ko, kp);
             load_to_lds(dst + BLKB + n * 1024, vo, vp);
         }
@@ -532,7 +545,7 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
             oacc[db] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pb, oacc[db], 0, 0, 0, 0, 0, 0);
         }
     }
-    merge_wavefronts<D, 4 * BLKB>(smem, oacc, m_run - DEC8_P_SHIFT, l_run, p, bhk, chunk, split);
+    merge_wavefronts<D, 4 * BLKB, DEC_WAVES>(smem, oacc, m_run - DEC8_P_SHIFT, l_run, p, bhk, chunk, split);
 }
 
 // One work-group (four wavefronts) per query row: merges the nsplit partials of the row, divides by l
@@ -607,6 +620,9 @@ __global__ __launch_bounds__(MRG_THREADS) void naut_decode_merge_kernel(const De
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             og[e] = acc[e] * inv_l;
+    } else if constexpr (EPT == 4) {
+        i32x2_t* og = (i32x2_t*)(orow + lane * EPT * 2);
+        *og = i32x2_t{In<DT_OUT>::pack2(acc[0] * inv_l, acc[1] * inv_l), In<DT_OUT>::pack2(acc[2] * inv_l, acc[3] * inv_l)};
     } else if constexpr (EPT == 2) {
         int* og = (int*)(orow + lane * EPT * 2);
         *og = In<DT_OUT>::pack2(acc[0] * inv_l, acc[1] * inv_l);
@@ -656,18 +672,20 @@ void* static_scratch(int* err)
     return ptr;
 }
 
+// D: the width the kernels are compiled for (64, 128 or 256)
 bool make_plan(int B, int Hq, int Hkv, int Sq, int Sk, int D, Plan* pl)
 {
+    const int W = dec_waves(D);
     const long long R = (long long)(Hq / Hkv) * Sq;
     const long long nchunks = (R + DEC_ROWS - 1) / DEC_ROWS;
     const long long nblk = ((long long)Sk + DEC_BLK - 1) / DEC_BLK;
     const long long base = (long long)B * Hkv * nchunks;
     long long nsplit = (DEC_TARGET_WGS + base - 1) / base;
-    const long long max_split = (nblk + 2 * DEC_WAVES - 1) / (2 * DEC_WAVES);  // at least two blocks per wavefront
+    const long long max_split = (nblk + 2 * W - 1) / (2 * W);  // at least two blocks per wavefront
     nsplit = nsplit > max_split ? max_split : nsplit;
     nsplit = nsplit < 1 ? 1 : nsplit;
     long long bps = (nblk + nsplit - 1) / nsplit;
-    bps = (bps + DEC_WAVES - 1) / DEC_WAVES * DEC_WAVES;
+    bps = (bps + W - 1) / W * W;
     nsplit = (nblk + bps - 1) / bps;
     if (nchunks > 65535 || (long long)B * Hkv > 65535 || nsplit > 0x7fffffffLL || R > 0x7fffffffLL)
         return false;
@@ -682,7 +700,7 @@ template <int D, int DT_IN, int DT_OUT>
 int launch_decode(const DecodeParams& p, hipStream_t stream)
 {
     const dim3 g1((unsigned)p.nsplit, (unsigned)p.nchunks, (unsigned)(p.B * p.Hkv));
-    hipLaunchKernelGGL((naut_decode_split_kernel<D, DT_IN>), g1, dim3(DEC_THREADS), 0, stream, p);
+    hipLaunchKernelGGL((naut_decode_split_kernel<D, DT_IN>), g1, dim3(dec_waves(D) * 64), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_launch(e);
@@ -701,8 +719,8 @@ extern "C" {
 size_t naut_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Sq, int Sk, int D)
 {
     Plan pl;
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || Hq % Hkv != 0 || D <= 0 || D % 8 != 0 || D > 128 ||
-        !make_plan(B, Hq, Hkv, Sq, Sk, D <= 64 ? 64 : 128, &pl))
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Sk <= 0 || Hq % Hkv != 0 || D <= 0 || D % 8 != 0 || D > 256 ||
+        !make_plan(B, Hq, Hkv, Sq, Sk, D <= 64 ? 64 : D <= 128 ? 128 : 256, &pl))
         return 0;
     return pl.ws_bytes;
 }
@@ -730,9 +748,9 @@ int decode_16bit(const void* q, const void* k, const void* v, void* o, float* ls
         return fail(NAUT_ERR_SHAPE, "scale must be finite");
     if (scale < 0.f)
         return fail(NAUT_ERR_UNSUPPORTED, "negative scale is not supported");
-    if (D % 8 != 0 || D > 128)
-        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 8, at most 128");
-    const int DK = D <= 64 ? 64 : 128;  // width the kernels are compiled for
+    if (D % 8 != 0 || D > 256)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 8, at most 256");
+    const int DK = D <= 64 ? 64 : D <= 128 ? 128 : 256;  // width the kernels are compiled for
     if ((in_dtype != NAUT_BF16 && in_dtype != NAUT_F16) || (out_dtype != in_dtype && out_dtype != NAUT_F32))
         return fail(NAUT_ERR_UNSUPPORTED, "supported dtypes: q/k/v bf16 or f16; o of the same type or f32");
     Plan pl;
@@ -823,6 +841,10 @@ int decode_16bit(const void* q, const void* k, const void* v, void* o, float* ls
 #define NAUT_DEC(DD, IN, OUT)                                  \
     if (DK == DD && in_dtype == IN && out_dtype == OUT)        \
         return launch_decode<DD, IN, OUT>(p, hs);
+    NAUT_DEC(256, NAUT_BF16, NAUT_BF16)
+    NAUT_DEC(256, NAUT_BF16, NAUT_F32)
+    NAUT_DEC(256, NAUT_F16, NAUT_F16)
+    NAUT_DEC(256, NAUT_F16, NAUT_F32)
     NAUT_DEC(128, NAUT_BF16, NAUT_BF16)
     NAUT_DEC(128, NAUT_BF16, NAUT_F32)
     NAUT_DEC(128, NAUT_F16, NAUT_F16)
@@ -847,9 +869,10 @@ int naut_attn_decode_strided(const void* q, const void* k, const void* v, void* 
                         in_dtype, out_dtype, st);
 }
 
-int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
-                         int Sq, int Sk, int D, int causal, float scale, float descale_q, float descale_k,
-                         float descale_v, void* workspace, size_t workspace_bytes, void* stream)
+int naut_attn_decode_fp8_strided(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq,
+                                 int Hkv, int Sq, int Sk, int D, int causal, float scale, float descale_q,
+                                 float descale_k, float descale_v, void* workspace, size_t workspace_bytes, void* stream,
+                                 const naut_strides* st)
 {
     if (!q || !k || !v || !o)
         return fail(NAUT_ERR_NULL, "q, k, v and o must be non-NULL device pointers");
@@ -863,10 +886,11 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
         return fail(NAUT_ERR_SHAPE, "scale and the three descale factors must be finite");
     if (scale < 0.f || descale_q <= 0.f || descale_k <= 0.f || descale_v <= 0.f)
         return fail(NAUT_ERR_UNSUPPORTED, "scale must be >= 0 and the descale factors > 0");
-    if (D != 64 && D != 128)
-        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    if (D % 16 != 0 || D > 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 16, at most 128");
+    const int DK = D <= 64 ? 64 : 128;  // width the kernels are compiled for
     Plan pl;  // over 64-key blocks: the plan of a cache half as long in 32-key blocks
-    if (!make_plan(B, Hq, Hkv, Sq, (Sk + 1) / 2, D, &pl))
+    if (!make_plan(B, Hq, Hkv, Sq, (Sk + 1) / 2, DK, &pl))
         return fail(NAUT_ERR_UNSUPPORTED, "shape exceeds the grid limits");
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)workspace) & 15)
         return fail(NAUT_ERR_ALIGN, "q, k, v, o and workspace must be 16-byte aligned");
@@ -876,6 +900,26 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
         return fail(NAUT_ERR_NULL, "workspace must be a non-NULL device pointer");
     if (workspace_bytes < pl.ws_bytes)
         return fail(NAUT_ERR_SHAPE, "workspace is smaller than naut_attn_decode_workspace_bytes()");
+
+    naut_strides cs;  // contiguous q, o [B][Hq][Sq][D] and k, v [B][Hkv][Sk][D]
+    cs.q_s = cs.k_s = cs.v_s = cs.o_s = D;
+    cs.q_h = cs.o_h = (long long)Sq * D;
+    cs.k_h = cs.v_h = (long long)Sk * D;
+    cs.q_b = cs.o_b = (long long)Hq * Sq * D;
+    cs.k_b = cs.v_b = (long long)Hkv * Sk * D;
+    if (!st)
+        st = &cs;
+    const long long in_strides[9] = {st->q_b, st->q_h, st->q_s, st->k_b, st->k_h, st->k_s, st->v_b, st->v_h, st->v_s};
+    for (long long x : in_strides)
+        if (x < 0 || x % 16 != 0)
+            return fail(NAUT_ERR_ALIGN, "q/k/v strides must be non-negative multiples of 16 elements (16 bytes)");
+    if (st->o_b <= 0 || st->o_h <= 0 || st->o_s <= 0 || st->o_b % 4 != 0 || st->o_h % 4 != 0 || st->o_s % 4 != 0)
+        return fail(NAUT_ERR_ALIGN, "o strides must be positive multiples of 4 elements");
+    if (st->q_s < D || st->k_s < D || st->v_s < D || st->o_s < D)
+        return fail(NAUT_ERR_SHAPE, "a sequence stride is smaller than D: rows would overlap");
+    const long long max_rs = 1LL << 23;  // elements: keeps 64 rows of byte offsets inside 32 bits
+    if (st->q_s > max_rs || st->k_s > max_rs || st->v_s > max_rs || st->o_s > max_rs)
+        return fail(NAUT_ERR_UNSUPPORTED, "sequence stride too large");
 
     DecodeParams p;
     p.q = q;
@@ -897,18 +941,24 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
     const float cc = scale * descale_q * descale_k * 1.4426950408889634f;
     p.c = cc > 0.f ? cc : 1.0e-30f;
     p.dv = descale_v;
-    // o: contiguous bf16 [B][Hq][Sq][D] (the merge kernel addresses it through strides); q, k, v: the split
-    // kernel indexes them as contiguous bytes itself
-    p.q_bs = p.q_hs = p.k_bs = p.k_hs = p.v_bs = p.v_hs = 0;
-    p.q_rs = p.k_rs = p.v_rs = 0;
-    p.o_bs = (long long)Hq * Sq * D * 2;
-    p.o_hs = (long long)Sq * D * 2;
-    p.o_rs = D * 2;
+    // q, k, v: one byte per element; o: bf16
+    p.q_bs = st->q_b;
+    p.q_hs = st->q_h;
+    p.q_rs = (int)st->q_s;
+    p.k_bs = st->k_b;
+    p.k_hs = st->k_h;
+    p.k_rs = (int)st->k_s;
+    p.v_bs = st->v_b;
+    p.v_hs = st->v_h;
+    p.v_rs = (int)st->v_s;
+    p.o_bs = st->o_b * 2;
+    p.o_hs = st->o_h * 2;
+    p.o_rs = (int)(st->o_s * 2);
     p.cpr = D / 8;
     hipStream_t hs = (hipStream_t)stream;
     const dim3 g1((unsigned)p.nsplit, (unsigned)p.nchunks, (unsigned)(p.B * p.Hkv));
     const dim3 g2((unsigned)p.R, (unsigned)(p.B * p.Hkv));
-    if (D == 128) {
+    if (DK == 128) {
         hipLaunchKernelGGL((naut_decode_split_fp8_kernel<128>), g1, dim3(DEC_THREADS), 0, hs, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
@@ -925,6 +975,16 @@ int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, f
     if (e != hipSuccess)
         return fail_launch(e);
     return NAUT_OK;
+}
+
+int naut_attn_decode_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,
+                         int Sq, int Sk, int D, int causal, float scale, float descale_q, float descale_k,
+                         float descale_v, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (D > 0 && D != 64 && D != 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128 (naut_attn_decode_fp8_strided takes other head dimensions)");
+    return naut_attn_decode_fp8_strided(q, k, v, o, lse, B, Hq, Hkv, Sq, Sk, D, causal, scale, descale_q, descale_k,
+                                        descale_v, workspace, workspace_bytes, stream, nullptr);
 }
 
 int naut_attn_decode_static(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv,

@@ -58,6 +58,11 @@ struct Fp8Params {
     // element, o: 2)
     long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
     int q_rs, k_rs, v_rs, o_rs;
+    // The kernels are compiled for D = 64 or 128; a narrower head runs on the next wider one (strided
+    // instantiation only): cpr16 16-byte chunks of every row are real, the chunks of Q beyond them read as
+    // zero, those of K and V repeat a real chunk (they meet zeros of Q, or end in columns of O that are
+    // not stored).
+    int cpr16;
 };
 
 // STRIDED = false: contiguous [B][H][S][D] tensors, every stride a compile-time constant (the launch
@@ -92,6 +97,7 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
 
     const int q_rs = STRIDED ? p.q_rs : D, k_rs = STRIDED ? p.k_rs : D, v_rs = STRIDED ? p.v_rs : D;
     const int o_rs = STRIDED ? p.o_rs : D * 2;
+    const int cpr16 = STRIDED ? p.cpr16 : CPR16;  // real 16-byte chunks per row
     const unsigned char* qg = (const unsigned char*)p.q + (STRIDED ? b * p.q_bs + hq * p.q_hs : (long long)bh * S * D);
     const unsigned char* kg =
         (const unsigned char*)p.k + (STRIDED ? b * p.k_bs + hk * p.k_hs : (long long)(b * p.Hkv + hk) * S * D);
@@ -106,8 +112,13 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     i32x8_t qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        const i32x4_t lo = *(const i32x4_t*)(qg + (size_t)my_q_ld * q_rs + ks * 64 + h * 32);
-        const i32x4_t hi = *(const i32x4_t*)(qg + (size_t)my_q_ld * q_rs + ks * 64 + h * 32 + 16);
+        const int c0 = ks * 4 + h * 2;  // this lane's two 16-byte chunks of the row
+        i32x4_t lo = *(const i32x4_t*)(qg + (size_t)my_q_ld * q_rs + (c0 < cpr16 ? c0 : 0) * 16);
+        i32x4_t hi = *(const i32x4_t*)(qg + (size_t)my_q_ld * q_rs + (c0 + 1 < cpr16 ? c0 + 1 : 0) * 16);
+        if (STRIDED && c0 >= cpr16)
+            lo = i32x4_t{0, 0, 0, 0};
+        if (STRIDED && c0 + 1 >= cpr16)
+            hi = i32x4_t{0, 0, 0, 0};
         qf[ks] = i32x8_t{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     }
 #pragma unroll
@@ -129,8 +140,9 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
         for (int i = 0; i < LD_PER_T; ++i) {
             const int L = tid + F8_THREADS * i;
             const int row = L / CPR16, c16 = L % CPR16;
-            gk_off[i] = row * k_rs + c16 * 16;
-            gv_off[i] = row * v_rs + c16 * 16;
+            const int cg = c16 < cpr16 ? c16 : cpr16 - 1;  // chunk read from memory
+            gk_off[i] = row * k_rs + cg * 16;
+            gv_off[i] = row * v_rs + cg * 16;
             st_k[i] = k8_off<D>(row, c16);
             st_v[i] = v8_off<D>(row, c16 >> 1) + (c16 & 1) * 16;
         }
@@ -154,8 +166,9 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
                 const int L = tid + F8_THREADS * i;
                 const int row = L / CPR16, c16 = L % CPR16;
                 const int rl = row < rows_last ? row : rows_last - 1;
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)(rl * k_rs + c16 * 16));
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)(rl * v_rs + c16 * 16));
+                const int cg = c16 < cpr16 ? c16 : cpr16 - 1;
+                kst[i] = *(const i32x4_t*)(kp + (unsigned)(rl * k_rs + cg * 16));
+                vst[i] = *(const i32x4_t*)(vp + (unsigned)(rl * v_rs + cg * 16));
             }
         } else {
 #pragma unroll
@@ -355,7 +368,7 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) {
             const int q = q_wave0 + i * RPI + ln / CPRO;
-            if (q < S)
+            if (q < S && (ln % CPRO) < 2 * cpr16)  // 16 bytes of bf16 O are 8 columns: two per real input chunk
                 *(i32x4_a8*)(o_bh + (size_t)q * o_rs + (ln % CPRO) * 16) = rows[i];
         }
     }
@@ -379,8 +392,9 @@ int naut_attn_fwd_fp8_strided(const void* q, const void* k, const void* v, void*
         return fail(NAUT_ERR_SHAPE, "scale and the three descale factors must be finite");
     if (scale < 0.f || descale_q <= 0.f || descale_k <= 0.f || descale_v <= 0.f)
         return fail(NAUT_ERR_UNSUPPORTED, "scale must be >= 0 and the descale factors > 0");
-    if (D != 64 && D != 128)
-        return fail(NAUT_ERR_UNSUPPORTED, "D must be 64 or 128");
+    if (D % 16 != 0 || D > 128)
+        return fail(NAUT_ERR_UNSUPPORTED, "D must be a multiple of 16, at most 128");
+    const int DK = D <= 64 ? 64 : 128;  // width the kernels are compiled for
     const long long nblocks = (long long)B * Hq * ((S + F8_BM - 1) / F8_BM);
     if ((long long)B * Hq > 0x7fffffffLL || nblocks > 0x7fffffffLL)
         return fail(NAUT_ERR_UNSUPPORTED, "B*Hq*ceil(S/128) exceeds the 1-D grid limit");
@@ -434,14 +448,15 @@ int naut_attn_fwd_fp8_strided(const void* q, const void* k, const void* v, void*
     const float c = scale * descale_q * descale_k * 1.4426950408889634f;
     p.c = c > 0.f ? c : 1e-30f;
     p.dv = descale_v;
+    p.cpr16 = D / 16;
     const dim3 grid((unsigned)nblocks);
     hipStream_t hs = (hipStream_t)stream;
     // contiguous tensors (whoever says so) take the instantiation with compile-time strides
-    const bool strided = st->q_b != cs.q_b || st->q_h != cs.q_h || st->q_s != cs.q_s || st->k_b != cs.k_b ||
+    const bool strided = D != DK || st->q_b != cs.q_b || st->q_h != cs.q_h || st->q_s != cs.q_s || st->k_b != cs.k_b ||
                          st->k_h != cs.k_h || st->k_s != cs.k_s || st->v_b != cs.v_b || st->v_h != cs.v_h ||
                          st->v_s != cs.v_s || st->o_b != cs.o_b || st->o_h != cs.o_h || st->o_s != cs.o_s;
 #define NAUT_F8_LAUNCH(DD, CC, SS)                                                          \
-    if (D == DD && (causal != 0) == CC && strided == SS)                                    \
+    if (DK == DD && (causal != 0) == CC && strided == SS)                                   \
         hipLaunchKernelGGL((naut_fwd_kernel_fp8<DD, CC, SS>), grid, dim3(F8_THREADS), 0, hs, p);
     NAUT_F8_LAUNCH(128, true, false)
     NAUT_F8_LAUNCH(128, false, false)

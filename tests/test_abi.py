@@ -109,7 +109,9 @@ def test_decode_argument_checks():
     assert nb.decode_workspace_bytes(1, 8, 3, 1, 4096, 128) == 0   # Hq % Hkv
     assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 96) == ws   # a narrower head runs on the 128-wide kernel
     assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 100) == 0   # D not a multiple of 8
-    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 136) == 0   # D too wide
+    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 136) > 0    # runs on the 256-wide kernel
+    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 136) == nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 256)
+    assert nb.decode_workspace_bytes(1, 8, 2, 1, 4096, 264) == 0   # D too wide
     ok = dict(B=1, Hq=8, Hkv=2, Sq=1, Sk=4096, D=128, causal=1, scale=0.1)
 
     def dec(q=A, k=A, v=A, o=A, lse=A, wsp=A, wsb=ws, **kw):
@@ -159,7 +161,7 @@ def test_decode_argument_checks():
     assert dec_s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED        # v row stride too large
     assert dec_s(good[:9] + (0,) + good[10:]) == nb.NAUT_ERR_ALIGN                   # o batch stride must be positive
     assert dec_s(good, D=100) == nb.NAUT_ERR_UNSUPPORTED
-    assert dec_s(good, D=136) == nb.NAUT_ERR_UNSUPPORTED
+    assert dec_s(good, D=264) == nb.NAUT_ERR_UNSUPPORTED
 
 
 def test_decode_fp8_argument_checks():
@@ -176,6 +178,22 @@ def test_decode_fp8_argument_checks():
     assert d8(k=A + 8) == nb.NAUT_ERR_ALIGN
     assert d8(wsp=None) == nb.NAUT_ERR_NULL
     assert d8(wsb=16) == nb.NAUT_ERR_SHAPE
+
+    # strided variant: any multiple of 16 up to 128, strides in bytes = elements
+    B, Hq, Hkv, Sq, Sk, D = 1, 8, 2, 1, 4096, 128
+    good = (Hq * Sq * D, Sq * D, D, Sk * Hkv * D, D, Hkv * D, Sk * Hkv * D, D, Hkv * D, Hq * Sq * D, Sq * D, D)
+
+    def d8s(strides, q=A, D=128, wsb=ws):
+        return nb.naut_attn_decode_fp8_strided_raw(q, A, A, A, A, B, Hq, Hkv, Sq, Sk, D, 1, 0.1, 1.0, 1.0, 1.0, A, wsb,
+                                                   None, strides)
+    assert d8s(good, q=None) == nb.NAUT_ERR_NULL
+    assert d8s(good, D=72) == nb.NAUT_ERR_UNSUPPORTED                                 # not a multiple of 16
+    assert d8s(good, D=144) == nb.NAUT_ERR_UNSUPPORTED                                # wider than the widest FP8 kernel
+    assert d8s(good[:5] + (Hkv * D + 8,) + good[6:]) == nb.NAUT_ERR_ALIGN            # k rows not 16-byte aligned
+    assert d8s(good[:5] + (D - 16,) + good[6:]) == nb.NAUT_ERR_SHAPE                 # k rows overlap
+    assert d8s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED          # v row stride too large
+    assert d8s(good[:9] + (0,) + good[10:]) == nb.NAUT_ERR_ALIGN                     # o batch stride must be positive
+    assert d8s(good, wsb=16) == nb.NAUT_ERR_SHAPE
 
 
 def test_strided_argument_checks():
@@ -209,7 +227,8 @@ def test_fp8_argument_checks():
     assert f8(Hkv=3) == nb.NAUT_ERR_SHAPE
     assert f8(dk=float("nan")) == nb.NAUT_ERR_SHAPE
     assert f8(dq=0.0) == nb.NAUT_ERR_UNSUPPORTED
-    assert f8(D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert f8(D=24) == nb.NAUT_ERR_UNSUPPORTED       # not a multiple of 16
+    assert f8(D=144) == nb.NAUT_ERR_UNSUPPORTED      # wider than the widest FP8 kernel
     assert f8(q=A + 4) == nb.NAUT_ERR_ALIGN
 
     def f8s(strides, **kw):
@@ -220,7 +239,7 @@ def test_fp8_argument_checks():
     H, S, D = 2, 128, 128
     good = (S * H * D, D, H * D) * 4                                                  # sequence-major
     assert f8s(good, q=None) == nb.NAUT_ERR_NULL
-    assert f8s(good, D=96) == nb.NAUT_ERR_UNSUPPORTED
+    assert f8s(good, D=72) == nb.NAUT_ERR_UNSUPPORTED
     assert f8s(good[:2] + (H * D + 8,) + good[3:]) == nb.NAUT_ERR_ALIGN              # q rows not 16-byte aligned
     assert f8s(good[:5] + (D - 16,) + good[6:]) == nb.NAUT_ERR_SHAPE                 # k rows overlap
     assert f8s(good[:8] + (1 << 24,) + good[9:]) == nb.NAUT_ERR_UNSUPPORTED          # v row stride too large

@@ -113,6 +113,8 @@ def _bshd(a, dt):
     (1, 16, 2, 5, 300, 128, True, synth.BF16, synth.F32),
     (3, 6, 3, 2, 2049, 64, True, synth.F16, synth.F16),
     (2, 4, 4, 7, 1000, 64, False, synth.BF16, synth.BF16),
+    (2, 8, 2, 1, 1500, 256, True, synth.BF16, synth.BF16),
+    (1, 6, 3, 2, 700, 192, True, synth.F16, synth.F32),
 ])
 def test_decode_sequence_major_cache(B, Hq, Hkv, Sq, Sk, D, causal, idt, odt):
     """K/V cache and queries stored [B][S][H][D]; O written in the same layout; the gaps of a padded O untouched."""
@@ -163,9 +165,20 @@ def test_decode_shared_cache_and_padded_rows():
     (80, 1, 16, 2, 5, 500, False, synth.F16, synth.F16),
     (96, 2, 4, 4, 1, 2049, True, synth.BF16, synth.BF16),
     (112, 1, 8, 1, 2, 1000, True, synth.F16, synth.F32),
+    (256, 1, 1, 1, 1, 1, False, synth.BF16, synth.BF16),       # the 256-wide kernel: one key
+    (256, 1, 2, 2, 1, 31, True, synth.BF16, synth.F32),        # less than one block
+    (256, 2, 8, 2, 1, 777, True, synth.BF16, synth.BF16),      # grouped-query, ragged last block
+    (256, 1, 16, 2, 5, 300, True, synth.F16, synth.F16),       # R = 40: two row chunks
+    (256, 1, 2, 2, 1, 4096, False, synth.BF16, synth.BF16),    # many splits
+    (256, 1, 2, 1, 64, 64, True, synth.F16, synth.F32),        # Sq == Sk, R = 128
+    (256, 3, 6, 3, 2, 2049, True, synth.BF16, synth.BF16),     # odd sizes everywhere
+    (136, 2, 4, 2, 1, 500, True, synth.BF16, synth.BF16),      # narrower heads on the 256-wide kernel
+    (192, 1, 8, 2, 3, 1000, True, synth.BF16, synth.F32),
+    (248, 1, 4, 4, 2, 333, False, synth.F16, synth.F16),
 ])
 def test_decode_other_head_dimensions(D, B, Hq, Hkv, Sq, Sk, causal, idt, odt):
-    """Multiples of 8 below 128 run on the 64- or 128-wide decode kernels (strided entry point, contiguous tensors)."""
+    """Multiples of 8 other than 64 and 128, up to 256, run on the next wider decode kernel (strided entry point,
+    contiguous tensors: a chunk read past a row's end would show up as the next row's data)."""
     q, k, v = make(B, Hq, Hkv, Sq, Sk, D, idt, 7700 + Sk + D, Sk // 50)
     scale = 1.0 / math.sqrt(D)
     qd, kd, vd = (gu.to_device(a, idt) for a in (q, k, v))
@@ -178,3 +191,19 @@ def test_decode_other_head_dimensions(D, B, Hq, Hkv, Sq, Sk, causal, idt, odt):
     torch.cuda.synchronize()
     o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, causal, scale)
     gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode D=%d" % D)
+
+
+def test_decode_long_cache_wide_heads():
+    """The benchmark's cache length at the widest head: B=2, 16 query heads on 4 K/V heads of D = 256, Sk = 16384."""
+    B, Hq, Hkv, Sq, Sk, D = 2, 16, 4, 1, 16384, 256
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, synth.BF16, 7878, Sk // 100)
+    scale = 1.0 / math.sqrt(D)
+    qd, kd, vd = (gu.to_device(a, synth.BF16) for a in (q, k, v))
+    od = torch.full((B, Hq, Sq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    nb.naut_attn_decode_strided(qd, kd, vd, od, lse, True, scale, ws)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, synth.BF16, True, scale)
+    gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode long D=256")
