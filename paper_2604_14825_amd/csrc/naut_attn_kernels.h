@@ -78,15 +78,6 @@ struct Params {
     int hao;       // kernel 1: (batch, head) pairs an XCD works on at a time (0: all of its share at once)
 };
 
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
 // S^T MFMAs of the variants that need more than 256 registers per lane (64 queries per wavefront in
 // kernel 2, D = 256 in kernel 1), written as asm so that their accumulator is an ordinary vector
 // register tuple while O and Q live in the accumulation registers (the compiler's own MFMA form

@@ -3,6 +3,8 @@
 #define NAUT_COMMON_H
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include <cstdint>
 
 #include "naut_attn.h"
@@ -75,6 +77,16 @@ __device__ __forceinline__ void load_to_lds(unsigned dst, int off, const unsigne
 #else
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(off), "s"(base) : "memory", "m0");
 #endif
+}
+
+// f(integral_constant<int, I>) for I = I0 .. N-1, unrolled at compile time
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
 }
 
 // ---- per-dtype pieces ------------------------------------------------------

@@ -21,7 +21,10 @@
 //     the factor cancels in O / l.  The conversion does not saturate (it makes NaN), hence the bound.
 //
 // Work decomposition as the 128-query kernel of naut_attn_kernels.h: 4 wavefronts x 32 queries per
-// work-group, 64-key tiles, register-staged loads, double-buffered LDS, one barrier per tile.
+// work-group, 64-key tiles.  K and V tiles go straight from global memory to LDS (global_load_lds_dwordx4,
+// the swizzle of the LDS layouts applied to the source address), F8_NBUF - 1 tiles ahead over a ring of
+// F8_NBUF buffers per operand: every wavefront waits for its own loads of the tile about to be used (vmcnt),
+// one barrier publishes them, and the buffer read in the previous step is refilled right after it.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -40,6 +43,10 @@ constexpr int F8_BM = 128;
 constexpr int F8_BN = 64;
 constexpr int F8_WAVES = 4;
 constexpr int F8_THREADS = F8_WAVES * 64;
+#ifndef NAUT_F8_NBUF
+#define NAUT_F8_NBUF 3
+#endif
+constexpr int F8_NBUF = NAUT_F8_NBUF;  // LDS buffers per operand: tiles are requested F8_NBUF - 1 steps ahead
 constexpr float F8_TAU = 1.0f;      // the reference maximum moves when a row exceeds it by more than 2^1
 constexpr float F8_P_SHIFT = 7.0f;  // P is formed as exp2(.. + 7): <= 2^(1+7) = 256, inside E4M3's range
 constexpr float F8_M_INIT = -1.0e30f;
@@ -72,12 +79,14 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
 {
     constexpr int TILEB = F8_BN * D;            // bytes per K or V tile
     constexpr int CPR16 = D / 16;               // 16-byte chunks per row
-    constexpr int LD_PER_T = F8_BN * CPR16 / F8_THREADS;
+    constexpr int NLDW = TILEB / 1024 / F8_WAVES;  // 1 KB direct loads per wavefront, tile and operand
+    constexpr int LA = F8_NBUF - 1;               // tiles in flight ahead of the one in use
     constexpr int KS = D / 64;                  // MFMA k-steps of Q.K^T (64 d-values each)
     constexpr int DB = D / 32;                  // 32-row blocks of O^T
-    static_assert(LD_PER_T >= 1, "every thread stages at least one chunk");
+    static_assert(NLDW >= 1, "every wavefront takes part in the tile loads");
+    static_assert(LA >= 1 && LA * 2 * NLDW < 64, "vmcnt field");
 
-    __shared__ __attribute__((aligned(256))) unsigned char smem[4 * TILEB];  // K0 V0 K1 V1
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[F8_NBUF * 2 * TILEB];  // K0 V0 K1 V1 ...
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -128,69 +137,44 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     const int kv_end = CAUSAL ? (S < (qt + 1) * F8_BM ? S : (qt + 1) * F8_BM) : S;
     const int ntiles = (kv_end + F8_BN - 1) / F8_BN;
 
-    // Register-staged tile loads.  Per-thread byte offsets inside a tile are fixed; the tile's base is
-    // wave-uniform, so a load is a scalar base plus a 32-bit lane offset.  Only the last tile of the
-    // sequence can be ragged: it takes a second set of offsets that re-read the last row, chosen by a
-    // uniform branch.  LDS store addresses are fixed too (the buffer offset is an immediate, the loop
-    // below is unrolled over the two buffers).
-    i32x4_t kst[LD_PER_T], vst[LD_PER_T];
-    int gk_off[LD_PER_T], gv_off[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
-    {
+    // Direct global->LDS tile loads.  Load n of a tile fills its physical 16-byte chunks 64n .. 64n+63, lane i
+    // the chunk 64n+i, so the lane fetches the logical chunk that k8_off / v8_off place there; wavefront w
+    // issues loads w*NLDW .. of both operands.  The tile's base is wave-uniform (a scalar), the lane's byte
+    // offset inside the tile is fixed; only the last tile of the sequence can be ragged: its offsets re-read
+    // the last row, chosen by a uniform branch.
+    int k_row[NLDW], k_col[NLDW], v_row[NLDW], v_col[NLDW];
 #pragma unroll
-        for (int i = 0; i < LD_PER_T; ++i) {
-            const int L = tid + F8_THREADS * i;
-            const int row = L / CPR16, c16 = L % CPR16;
-            const int cg = c16 < cpr16 ? c16 : cpr16 - 1;  // chunk read from memory
-            gk_off[i] = row * k_rs + cg * 16;
-            gv_off[i] = row * v_rs + cg * 16;
-            st_k[i] = k8_off<D>(row, c16);
-            st_v[i] = v8_off<D>(row, c16 >> 1) + (c16 & 1) * 16;
-        }
+    for (int i = 0; i < NLDW; ++i) {
+        const int P = (wave * NLDW + i) * 64 + lane;
+        const int r = P / CPR16, pc = P % CPR16;
+        const int kc = pc ^ ((r >> 1) & (CPR16 - 1));  // the inverse of k8_off
+        const int key = D == 128 ? (((r >> 1) & 1) | (((r >> 3) & 1) << 1)) : ((r >> 3) & 1);
+        const int vc = (((pc >> 1) ^ key) << 1) + (pc & 1);  // the inverse of v8_off (32-byte chunks, two halves)
+        k_row[i] = v_row[i] = r;
+        k_col[i] = (kc < cpr16 ? kc : cpr16 - 1) * 16;
+        v_col[i] = (vc < cpr16 ? vc : cpr16 - 1) * 16;
     }
+    const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
+    const unsigned ld_dst = smem_base + (unsigned)(wave * NLDW * 1024);
     const int last_tile = (S + F8_BN - 1) / F8_BN - 1;
     const int rows_last = S - last_tile * F8_BN;  // rows of the sequence's last tile, >= 1
-    auto g_load = [&](int tile) {
-        // the tile offset is pinned in scalar registers: otherwise it is folded into 64-bit per-lane
-        // addresses computed with vector instructions for every load
-        // (contiguous tensors: K and V share every offset)
-        size_t koff = (size_t)tile * F8_BN * k_rs, voff = STRIDED ? (size_t)tile * F8_BN * v_rs : 0;
-        asm volatile("" : "+s"(koff));
-        if constexpr (STRIDED)
-            asm volatile("" : "+s"(voff));
-        const unsigned char* kp = kg + koff;
-        const unsigned char* vp = vg + (STRIDED ? voff : koff);
+    auto issue_tile = [&](int tile, auto BUFC) {
+        constexpr unsigned KB_OFF = decltype(BUFC)::value * 2 * TILEB;
+        const unsigned char* kp = kg + (size_t)tile * F8_BN * k_rs;
+        const unsigned char* vp = vg + (size_t)tile * F8_BN * v_rs;
         if (tile == last_tile) {
 #pragma unroll
-            for (int i = 0; i < LD_PER_T; ++i) {
-                // recomputed here rather than kept in registers for the whole kernel
-                const int L = tid + F8_THREADS * i;
-                const int row = L / CPR16, c16 = L % CPR16;
-                const int rl = row < rows_last ? row : rows_last - 1;
-                const int cg = c16 < cpr16 ? c16 : cpr16 - 1;
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)(rl * k_rs + cg * 16));
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)(rl * v_rs + cg * 16));
+            for (int i = 0; i < NLDW; ++i) {
+                const int rl = k_row[i] < rows_last ? k_row[i] : rows_last - 1;
+                load_to_lds(ld_dst + KB_OFF + i * 1024, rl * k_rs + k_col[i], kp);
+                load_to_lds(ld_dst + KB_OFF + TILEB + i * 1024, rl * v_rs + v_col[i], vp);
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < LD_PER_T; ++i) {
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)gk_off[i]);
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)(STRIDED ? gv_off[i] : gk_off[i]));
+            for (int i = 0; i < NLDW; ++i) {
+                load_to_lds(ld_dst + KB_OFF + i * 1024, k_row[i] * k_rs + k_col[i], kp);
+                load_to_lds(ld_dst + KB_OFF + TILEB + i * 1024, v_row[i] * v_rs + v_col[i], vp);
             }
-        }
-    };
-    const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
-#pragma unroll
-    for (int i = 0; i < LD_PER_T; ++i) {
-        st_k[i] += (int)smem_base;
-        st_v[i] += (int)smem_base;
-        asm volatile("" : "+v"(st_k[i]), "+v"(st_v[i]));  // opaque: buffer offsets stay instruction immediates
-    }
-    auto s_store = [&](auto BUFC) {
-        constexpr int KB_OFF = decltype(BUFC)::value * 2 * TILEB;
-#pragma unroll
-        for (int i = 0; i < LD_PER_T; ++i) {
-            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_k[i] + KB_OFF) = kst[i];
-            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_v[i] + KB_OFF + TILEB) = vst[i];
         }
     };
 
@@ -226,17 +210,30 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     float l_run = 0.f;
     i32x8_t pb = {0, 0, 0, 0, 0, 0, 0, 0};  // P of the current tile as the B operand (lives across tiles, see pack4_fp8)
 
-    g_load(0);
-    s_store(std::integral_constant<int, 0>{});
-    __syncthreads();
+    // prologue: the first LA tiles
+    static_for<0, LA>([&](auto T) {
+        if (decltype(T)::value < ntiles)
+            issue_tile(decltype(T)::value, T);
+    });
 
-    // one key tile; BUFC = j & 1 as a constant (the driver loop below alternates the two instances)
+    // one key tile; BUFC = j % F8_NBUF as a constant (the driver loop below is unrolled over the buffers)
     auto step = [&](auto BUFC, int j) {
         constexpr int BUF = decltype(BUFC)::value;
         constexpr int KT = BUF * 2 * TILEB, VT = KT + TILEB;  // byte offsets of this step's K and V tiles
         const int kv0 = j * F8_BN;
-        if (j + 1 < ntiles)
-            g_load(j + 1);
+        // Tile j must have landed.  Loads complete in order, so with the tiles j+1 .. j+LA-1 requested after it
+        // this wavefront may leave their loads in flight; near the end fewer were requested and it waits for all.
+        if (j + LA - 1 < ntiles)
+            wait_loads<(LA - 1) * 2 * NLDW>();
+        else
+            wait_loads<0>();
+        tile_barrier();  // publishes tile j; every wavefront is done with the buffer of tile j-1, refilled next
+        if (j + LA < ntiles)
+            issue_tile(j + LA, std::integral_constant<int, (BUF + LA) % F8_NBUF>{});
+        if constexpr (SAFE_SYNC) {  // checking build: nothing in flight while a step computes
+            wait_loads<0>();
+            tile_barrier();
+        }
 
         const bool active = !CAUSAL || kv0 <= q_wave0 + 31;
         if (active) {
@@ -315,15 +312,13 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
                 oacc[db] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pb, oacc[db], 0, 0, 0, 0, 0, 0);
             }
         }
-        if (j + 1 < ntiles)
-            s_store(std::integral_constant<int, BUF ^ 1>{});
-        __syncthreads();
     };
-    for (int j = 0; j < ntiles; j += 2) {
-        step(std::integral_constant<int, 0>{}, j);
-        if (j + 1 < ntiles)
-            step(std::integral_constant<int, 1>{}, j + 1);
-    }
+    for (int j = 0; j < ntiles; j += F8_NBUF)
+        static_for<0, F8_NBUF>([&](auto B_) {
+            if (j + decltype(B_)::value < ntiles)
+                step(B_, j + decltype(B_)::value);
+        });
+    __syncthreads();  // the tiles are dead from here on: the epilogue stages O in them
 
     // Epilogue: one division by l (the 2^7 of P cancels), times descale_v; lse undoes the shift.
     const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -335,7 +330,7 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
     // are dead after the loop's last barrier; each wavefront stages its 32 rows in its own quarter of them.
     {
         constexpr int ROWB_O = D * 2, CPRO = D / 8, R256 = ROWB_O >= 256 ? 1 : 256 / ROWB_O;
-        static_assert(F8_WAVES * 32 * ROWB_O <= 4 * TILEB, "staging rows must fit the tile buffers");
+        static_assert(F8_WAVES * 32 * ROWB_O <= F8_NBUF * 2 * TILEB, "staging rows must fit the tile buffers");
         // Every address below derives from this copy of the lane id, which exists only from here on: nothing
         // of the epilogue can be computed before the key loop and held in registers across it.
         int ln = lane;

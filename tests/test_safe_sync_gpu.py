@@ -136,3 +136,74 @@ def test_decode_bit_identical(B, Hq, Hkv, Sq, Sk, D):
         torch.cuda.synchronize()
         outs.append((o.view(torch.int16).cpu().numpy(), lse.view(torch.int32).cpu().numpy()))
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]), "decode differs"
+
+
+F8_SCALES = (1.0 / 64, 1.0 / 8, 1.0 / 64)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D,causal", [(1, 1, 1, 1, 64, False), (1, 2, 1, 63, 128, True), (2, 2, 2, 64, 64, False),
+                                               (1, 2, 2, 65, 128, False), (2, 4, 2, 129, 128, True), (1, 3, 1, 200, 64, True),
+                                               (1, 2, 2, 257, 128, False), (1, 8, 2, 400, 96, True), (1, 4, 4, 1024, 128, True),
+                                               (1, 4, 2, 777, 48, False)])
+def test_fp8_prefill_bit_identical(B, Hq, Hkv, S, D, causal):
+    """The FP8 prefill kernel: direct loads a ring of buffers ahead, each wavefront counting its own; S from one
+    tile to sixteen covers every phase of the ring and the ragged last tile."""
+    dq, dk, dv = F8_SCALES
+    q = synth.fill_e4m3(B, Hq, S, D, 26000 + S, synth.TAG_Q, dq)
+    k = synth.fill_e4m3(B, Hkv, S, D, 26000 + S, synth.TAG_K, dk, S // 50, 8.0)
+    v = synth.fill_e4m3(B, Hkv, S, D, 26000 + S, synth.TAG_V, dv)
+    qd, kd, vd = (torch.from_numpy(a).cuda() for a in (q, k, v))
+    outs = []
+    print("safe-sync fp8", B, Hq, Hkv, S, D, causal, flush=True)
+    for L in libs():
+        o = torch.full((B, Hq, S, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((B, Hq, S), float("nan"), dtype=torch.float32, device="cuda")
+        rc = L.naut_attn_fwd_fp8(qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), o.data_ptr(), lse.data_ptr(), B, Hq, Hkv, S, D,
+                                 int(causal), 1.0 / math.sqrt(D), dq, dk, dv, None)
+        assert rc == 0, L.naut_last_error_string()
+        torch.cuda.synchronize()
+        outs.append((o.view(torch.int16).cpu().numpy(), lse.view(torch.int32).cpu().numpy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]), "fp8 prefill differs"
+
+
+def test_fp8_every_tile_count_bit_identical():
+    dq, dk, dv = F8_SCALES
+    for t in range(1, 9):
+        for S in (64 * t - 1, 64 * t, 64 * t + 1):
+            q = synth.fill_e4m3(1, 2, S, 128, 27000 + S, synth.TAG_Q, dq)
+            k = synth.fill_e4m3(1, 1, S, 128, 27000 + S, synth.TAG_K, dk)
+            v = synth.fill_e4m3(1, 1, S, 128, 27000 + S, synth.TAG_V, dv)
+            qd, kd, vd = (torch.from_numpy(a).cuda() for a in (q, k, v))
+            outs = []
+            print("safe-sync fp8 tiles", S, flush=True)
+            for L in libs():
+                o = torch.full((1, 2, S, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+                rc = L.naut_attn_fwd_fp8(qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), o.data_ptr(), None, 1, 2, 1, S, 128, 1,
+                                         1.0 / math.sqrt(128), dq, dk, dv, None)
+                assert rc == 0, L.naut_last_error_string()
+                torch.cuda.synchronize()
+                outs.append(o.view(torch.int16).cpu().numpy())
+            assert np.array_equal(outs[0], outs[1]), "fp8 prefill differs at S = %d" % S
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D", [(1, 4, 4, 1, 100, 128), (2, 8, 2, 1, 777, 128), (1, 8, 1, 3, 500, 64),
+                                            (2, 32, 8, 1, 16384, 128)])
+def test_fp8_decode_bit_identical(B, Hq, Hkv, Sq, Sk, D):
+    dq, dk, dv = F8_SCALES
+    q = synth.fill_e4m3(B, Hq, Sq, D, 28000 + Sk, synth.TAG_Q, dq)
+    k = synth.fill_e4m3(B, Hkv, Sk, D, 28000 + Sk, synth.TAG_K, dk, Sk // 50, 8.0)
+    v = synth.fill_e4m3(B, Hkv, Sk, D, 28000 + Sk, synth.TAG_V, dv)
+    qd, kd, vd = (torch.from_numpy(a).cuda() for a in (q, k, v))
+    outs = []
+    print("safe-sync fp8 decode", B, Hq, Hkv, Sq, Sk, D, flush=True)
+    for L in libs():
+        o = torch.full((B, Hq, Sq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+        nbytes = L.naut_attn_decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D)
+        ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+        rc = L.naut_attn_decode_fp8(qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), o.data_ptr(), lse.data_ptr(), B, Hq, Hkv, Sq, Sk,
+                                    D, 1, 1.0 / math.sqrt(D), dq, dk, dv, ws.data_ptr(), nbytes, None)
+        assert rc == 0, L.naut_last_error_string()
+        torch.cuda.synchronize()
+        outs.append((o.view(torch.int16).cpu().numpy(), lse.view(torch.int32).cpu().numpy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]), "fp8 decode differs"
