@@ -46,6 +46,10 @@
 #include "naut_attn.h"
 #include "naut_common.h"
 
+#ifndef NAUT_K1_NBUF
+#define NAUT_K1_NBUF 2
+#endif
+
 namespace naut_k {
 
 using namespace naut;
@@ -128,18 +132,20 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     constexpr int ROWB = D * 2;              // bytes per K/V row
     constexpr int TILEB = BN * ROWB;         // bytes per K or V tile
     constexpr int CPR = D / 8;               // 16-byte chunks per row
-    constexpr int LD_PER_T = BN * CPR / NTHREADS;  // chunks per thread per tile
     constexpr int KS = D / 16;               // MFMA k-steps of Q.K^T
     constexpr int DB = D / 32;               // 32-row blocks of O^T
     constexpr int KB = BN / 32;              // 32-key blocks of S^T
 
-    // D <= 128: K0 V0 K1 V1, filled through registers.  D = 256: four K buffers, then four V buffers,
-    // filled by direct global->LDS loads issued three steps ahead (one wavefront per SIMD has nothing
-    // else to hide the load latency behind, and no registers to stage tiles in).
+    // Tiles are filled by direct global->LDS loads, each wavefront its share of every tile.  D = 256: four K
+    // buffers, then four V buffers, filled three steps ahead (one wavefront per SIMD has nothing else to
+    // hide the load latency behind).  D <= 128: K0 V0 K1 V1 ..., a ring of NB2 buffers filled NB2 - 1 steps
+    // ahead (the key loop is unrolled over the ring, so a tile's LDS offsets are instruction immediates).
     constexpr bool WIDE = D > 128;
     constexpr int NB = 4;                          // buffers per operand (wide)
-    constexpr int LDW = TILEB / 1024 / NWAVES;     // direct loads (1 KB each) per wavefront per tile (wide)
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[(WIDE ? 2 * NB : 4) * TILEB];
+    constexpr int NB2 = NAUT_K1_NBUF;              // buffers per operand (D <= 128)
+    constexpr int LDW = TILEB / 1024 / NWAVES;     // direct loads (1 KB each) per wavefront per tile
+    static_assert(LDW >= 1 && (NB2 - 1) * 2 * LDW < 64, "every wavefront loads; vmcnt field");
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[(WIDE ? 2 * NB : 2 * NB2) * TILEB];
     __shared__ float dl_lds[NTHREADS];
 
     const int tid = threadIdx.x;
@@ -215,44 +221,77 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
     const int kv_end = CAUSAL ? (S < (qt + 1) * BM ? S : (qt + 1) * BM) : S;
     const int ntiles = (kv_end + BN - 1) / BN;
 
-    // wide: lane i of direct load n fills physical chunk P = (wave*LDW + n)*64 + i of the tile, so it
-    // fetches the logical (row, chunk) that k_off / v_off place there.
+    // Lane i of direct load n fills physical chunk P = (wave*LDW + n)*64 + i of the tile, so it fetches the
+    // logical (row, chunk) that k_off / v_off place there (chunks beyond a narrower head repeat a real one).
+    auto source_of = [&](int n, int& krow, int& kcol, int& vrow, int& vcol) {
+        const int P = (wave * LDW + n) * 64 + lane;
+        int kc, vc;
+        if constexpr (WIDE) {
+            const int line = P >> 4;
+            krow = line >> 1;
+            kc = ((line & 1) << 4) | ((P & 15) ^ (krow & 15));
+            vrow = P >> 5;
+            vc = (P & 31) ^ ((vrow & 3) << 2);
+        } else {
+            const int line = P >> 4, pos = P & 15;
+            const int off = ((line << 4) + (pos ^ (line & 15))) * 16;  // the inverse of k_off: byte offset in a dense tile
+            krow = off / ROWB;
+            kc = off % ROWB / 16;
+            vrow = P / CPR;                                              // the inverse of v_off
+            vc = D == 128 ? (P % CPR) ^ ((vrow & 3) << 2) : (P % CPR) ^ (((vrow >> 1) & 1) << 2);
+        }
+        kcol = (kc < cpr ? kc : cpr - 1) * 16;
+        vcol = (vc < cpr ? vc : cpr - 1) * 16;
+    };
+    // wide: (row, byte in the row) per load; D <= 128: the byte offset inside a whole tile
     int wk_row[LDW], wk_col[LDW], wv_row[LDW], wv_col[LDW];
     const unsigned smem_base = (unsigned)(uintptr_t)(NAUT_LDS unsigned char*)smem;
-    if constexpr (WIDE) {
 #pragma unroll
-        for (int n = 0; n < LDW; ++n) {
-            const int P = (wave * LDW + n) * 64 + lane;
-            const int line = P >> 4, krow = line >> 1;
-            const int kc = ((line & 1) << 4) | ((P & 15) ^ (krow & 15));
-            wk_row[n] = krow;
-            wk_col[n] = (kc < cpr ? kc : cpr - 1) * 16;
-            const int vrow = P >> 5;
-            const int vc = (P & 31) ^ ((vrow & 3) << 2);
-            wv_row[n] = vrow;
-            wv_col[n] = (vc < cpr ? vc : cpr - 1) * 16;
+    for (int n = 0; n < LDW; ++n) {
+        source_of(n, wk_row[n], wk_col[n], wv_row[n], wv_col[n]);
+        if constexpr (!WIDE) {
+            wk_col[n] += wk_row[n] * p.k_rs;
+            wv_col[n] += wv_row[n] * p.v_rs;
         }
     }
+    const int last_tile = (S + BN - 1) / BN - 1;  // of the sequence: the only one that can be ragged
     // The address of a load is the tile's base, a 64-bit wave-uniform pointer, plus a 32-bit lane offset inside
     // the tile (at most BN rows of the largest row stride the entry point admits); rows beyond the end of the
     // sequence re-read its last row.
-    auto issue_tile = [&](int tile) {
-        const unsigned kd = smem_base + (unsigned)((tile % NB) * TILEB + wave * LDW * 1024);
-        const unsigned vd = kd + NB * TILEB;
+    // (D <= 128: `buf`, the tile's place in the ring, is a constant at every call)
+    auto issue_tile = [&](int tile, int buf = 0) {
+        const unsigned kd = smem_base + (unsigned)((WIDE ? (tile % NB) * TILEB : buf * 2 * TILEB) + wave * LDW * 1024);
+        const unsigned vd = kd + (WIDE ? NB * TILEB : TILEB);
         const unsigned char* const kt = kg + (size_t)tile * BN * p.k_rs;
         const unsigned char* const vt = vg + (size_t)tile * BN * p.v_rs;
         const int last_row = S - 1 - tile * BN;  // of this tile, counted from its first row; >= 0
+        if constexpr (WIDE) {
 #pragma unroll
-        for (int n = 0; n < LDW; ++n) {
-            const int row = wk_row[n] < last_row ? wk_row[n] : last_row;
-            const int off = row * p.k_rs + wk_col[n];
-            load_to_lds(kd + n * 1024, off, kt);
-        }
+            for (int n = 0; n < LDW; ++n) {
+                const int row = wk_row[n] < last_row ? wk_row[n] : last_row;
+                const int off = row * p.k_rs + wk_col[n];
+                load_to_lds(kd + n * 1024, off, kt);
+            }
 #pragma unroll
-        for (int n = 0; n < LDW; ++n) {
-            const int row = wv_row[n] < last_row ? wv_row[n] : last_row;
-            const int off = row * p.v_rs + wv_col[n];
-            load_to_lds(vd + n * 1024, off, vt);
+            for (int n = 0; n < LDW; ++n) {
+                const int row = wv_row[n] < last_row ? wv_row[n] : last_row;
+                const int off = row * p.v_rs + wv_col[n];
+                load_to_lds(vd + n * 1024, off, vt);
+            }
+        } else if (tile == last_tile) {  // once per work-group: the offsets of the ragged tile are formed on the spot
+#pragma unroll
+            for (int n = 0; n < LDW; ++n) {
+                int kr, kcol, vr, vcol;
+                source_of(n, kr, kcol, vr, vcol);
+                load_to_lds(kd + n * 1024, (kr < last_row ? kr : last_row) * p.k_rs + kcol, kt);
+                load_to_lds(vd + n * 1024, (vr < last_row ? vr : last_row) * p.v_rs + vcol, vt);
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < LDW; ++n) {
+                load_to_lds(kd + n * 1024, wk_col[n], kt);
+                load_to_lds(vd + n * 1024, wv_col[n], vt);
+            }
         }
     };
     // Waits until at most `ahead` later tiles of this wavefront's loads are still in flight.
@@ -265,58 +304,6 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             wait_loads<0>();
     };
 
-    // D <= 128: global -> register staging of one K and one V tile.  A load is a wave-uniform tile base
-    // plus a fixed 32-bit lane offset; the last tile of the sequence, which may be ragged, has offsets of
-    // its own that re-read the last row (chosen by a uniform branch).  LDS store addresses are fixed
-    // registers plus the buffer offset as an immediate (the key loop is unrolled over the buffers).
-    i32x4_t kst[LD_PER_T], vst[LD_PER_T];
-    int gk_off[LD_PER_T], gv_off[LD_PER_T], st_k[LD_PER_T], st_v[LD_PER_T];
-    const int last_tile = (S + BN - 1) / BN - 1;
-    const int rows_left = S - last_tile * BN;  // rows of the sequence's last tile, >= 1
-    if constexpr (!WIDE) {
-#pragma unroll
-        for (int i = 0; i < LD_PER_T; ++i) {
-            const int L = tid + NTHREADS * i;
-            const int row = L / CPR;
-            const int ch = (L % CPR < cpr ? L % CPR : cpr - 1) * 16;
-            gk_off[i] = row * p.k_rs + ch;
-            gv_off[i] = row * p.v_rs + ch;
-            st_k[i] = (int)smem_base + k_off<D>(row, L % CPR);
-            st_v[i] = (int)smem_base + v_off<D>(row, L % CPR);
-            asm volatile("" : "+v"(st_k[i]), "+v"(st_v[i]));  // opaque: buffer offsets stay instruction immediates
-        }
-    }
-    auto g_load = [&](int tile) {
-        // tile offsets pinned in scalar registers: otherwise they are folded into 64-bit per-lane
-        // addresses computed with vector instructions for every load
-        size_t koff = (size_t)tile * BN * p.k_rs, voff = (size_t)tile * BN * p.v_rs;
-        asm volatile("" : "+s"(koff), "+s"(voff));
-        const unsigned char* kp = kg + koff;
-        const unsigned char* vp = vg + voff;
-        if (tile == last_tile) {  // once per work-group: the offsets of the ragged tile are formed on the spot
-#pragma unroll
-            for (int i = 0; i < LD_PER_T; ++i) {
-                const int row = (tid + NTHREADS * i) / CPR;
-                const int back = row < rows_left ? 0 : row - (rows_left - 1);  // rows to step back to the last real one
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)(gk_off[i] - back * p.k_rs));
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)(gv_off[i] - back * p.v_rs));
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < LD_PER_T; ++i) {
-                kst[i] = *(const i32x4_t*)(kp + (unsigned)gk_off[i]);
-                vst[i] = *(const i32x4_t*)(vp + (unsigned)gv_off[i]);
-            }
-        }
-    };
-    auto s_store = [&](auto BUFC) {
-        constexpr int OFF = decltype(BUFC)::value * 2 * TILEB;
-#pragma unroll
-        for (int i = 0; i < LD_PER_T; ++i) {
-            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_k[i] + OFF) = kst[i];
-            *(NAUT_LDS i32x4_t*)(uintptr_t)(st_v[i] + OFF + TILEB) = vst[i];
-        }
-    };
     // fixed LDS addresses of this lane's fragment reads in buffer 0 (K: per k-step; V: per 32-row block
     // of O^T, first of the two transposed reads); buffer, key-block and key-step offsets are immediates
     // (adding 8, 16 or 32 to a row changes no swizzle key)
@@ -366,18 +353,19 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         wait_tiles(ntiles - 1);
         tile_barrier();
     } else {
-        g_load(0);
+        static_for<0, NB2 - 1>([&](auto TC) {
+            if (decltype(TC)::value < ntiles)
+                issue_tile(decltype(TC)::value, decltype(TC)::value);
+        });
         int cpr_late = cpr;
-        asm volatile("" : "+s"(cpr_late));  // ordered after the asm inside g_load: so is everything that uses it
-        pin_q(cpr_late);
-        s_store(std::integral_constant<int, 0>{});
-        __syncthreads();
+        asm volatile("" : "+s"(cpr_late));  // ordered after the asm of the tile loads: so is everything that uses it
+        pin_q(cpr_late);                    // Q and the first tiles share one round trip to memory
     }
 
     // One key tile.  D <= 128: UC = j & 1 as a constant -- the driver loop below is unrolled over the two
     // LDS buffers, so the tile's LDS offsets are immediates.  D = 256 keeps one copy of its (long) body
     // and adds the buffer offset at run time.
-    constexpr int NU = WIDE ? 1 : 2;
+    constexpr int NU = WIDE ? 1 : NB2;
     auto step = [&](auto UC, int j) {
         constexpr int U = decltype(UC)::value;
         const int KT = WIDE ? (j % NB) * TILEB : U * 2 * TILEB;   // byte offset of this step's K tile
@@ -389,8 +377,21 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                 issue_tile(j + NB - 1);
             if constexpr (SAFE_SYNC)
                 tile_barrier();  // checking build: nothing in flight while the step computes
-        } else if (j + 1 < ntiles)
-            g_load(j + 1);
+        } else {
+            // Tile j must have landed.  Loads complete in order, so with the tiles j+1 .. j+NB2-2 requested after
+            // it this wavefront may leave theirs in flight; near the end fewer were requested and it waits for all.
+            if (j + NB2 - 2 < ntiles)
+                wait_loads<(NB2 - 2) * 2 * LDW>();
+            else
+                wait_loads<0>();
+            tile_barrier();  // publishes tile j; every wavefront has left step j-1, whose buffer is refilled next
+            if (j + NB2 - 1 < ntiles)
+                issue_tile(j + NB2 - 1, (U + NB2 - 1) % NB2);
+            if constexpr (SAFE_SYNC) {  // checking build: nothing in flight while the step computes
+                wait_loads<0>();
+                tile_barrier();
+            }
+        }
 
         // Causal block skipping per wavefront: nothing to do if every key of the tile lies
         // beyond this wavefront's last query.
@@ -520,10 +521,6 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             // would wait for all tile loads in flight.
             wait_tiles(ntiles - 2 - j);
             tile_barrier();
-        } else {
-            if (j + 1 < ntiles)
-                s_store(std::integral_constant<int, U ^ 1>{});
-            __syncthreads();
         }
     };
     for (int j0 = 0; j0 < ntiles; j0 += NU) {
@@ -534,6 +531,8 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
         });
     }
 
+    if constexpr (!WIDE)
+        __syncthreads();  // every wavefront has left the last step: the tiles are dead, the epilogue stages O in them
     // Epilogue: one division by l (the per-step divide/multiply pairs telescope away), lse, store.
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float dl_run = dl_slot();
