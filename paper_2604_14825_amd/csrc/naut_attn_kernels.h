@@ -1352,16 +1352,20 @@ inline int pick_variant(int S, long long nbh, int D, int causal)
     // 256..16384, 2..512 heads, both head dimensions, with and without the causal mask.  The
     // pipelined 256-query kernel halves the K/V traffic per FLOP but pays a fill and a drain stage
     // per work-group and needs a full wave of work-groups: it wins once there is one work-group per
-    // CU and the key loop is long enough.  At D = 128 that is an average of 512 keys per query
-    // without the mask and 1024 with it (the 128-query tiles follow the causal diagonal more
-    // closely); at D = 64, where the softmax and not the MFMAs sets the pace and the 128-query
-    // kernel keeps three wavefronts per SIMD, only from 8192 keys per query.  The
+    // CU and the key loop is long enough.  At D = 128 that is an average of 1024 keys per query
+    // without the mask and 2048 with it (the 128-query tiles follow the causal diagonal more
+    // closely).  At D = 64 the softmax and not the MFMAs sets the pace and the 128-query kernel keeps
+    // four wavefronts per SIMD: the pipelined kernel is ahead only on long key loops (8192 keys per
+    // query) with few work-groups (fewer than four 256-query tiles per CU).  The
     // 64-queries-per-wavefront variant is within 2 % of the fastest where it wins at all and is
     // selectable by name only.
     const long long wg256 = nbh * ((S + BM2 - 1) / BM2);
     const int avg_keys = causal ? (S + 1) / 2 : S;
-    const int min_keys = D > 64 ? (causal ? 1024 : 512) : 8192;
-    return (wg256 >= 256 && avg_keys >= min_keys) ? V_W8Q32 : V_BM128;
+    if (wg256 < 256)
+        return V_BM128;
+    if (D > 64)
+        return avg_keys >= (causal ? 2048 : 1024) ? V_W8Q32 : V_BM128;
+    return (avg_keys >= 8192 && wg256 < 1024) ? V_W8Q32 : V_BM128;
 }
 
 template <int D, int DT_IN, int DT_OUT>

@@ -45,10 +45,12 @@ def test_variant_rule_and_override(monkeypatch):
     assert nb.variant_name(1, 32, 16384, 128, True, bf, bf) == big                       # long
     assert nb.variant_name(1, 512, 512, 128, True, bf, bf) == small                      # many heads, short causal loop
     assert nb.variant_name(1, 8, 4096, 128, False, bf, bf) == small                      # too few work-groups for 256 CUs
-    assert nb.variant_name(1, 512, 1024, 128, True, bf, bf) == small                     # causal: 512 keys per query on average
-    assert nb.variant_name(1, 512, 1024, 128, False, bf, bf) == big                      # the same shape without the mask
+    assert nb.variant_name(1, 128, 2048, 128, True, bf, bf) == small                     # causal: 1024 keys per query on average
+    assert nb.variant_name(1, 128, 2048, 128, False, bf, bf) == big                      # the same shape without the mask
+    assert nb.variant_name(1, 128, 512, 128, False, bf, bf) == small
     assert nb.variant_name(1, 32, 8192, 64, True, bf, bf) == small                       # D = 64: the softmax sets the pace
-    assert nb.variant_name(1, 32, 16384, 64, True, bf, bf) == big
+    assert nb.variant_name(1, 32, 16384, 64, True, bf, bf) == small                      # ... even on long loops with many work-groups
+    assert nb.variant_name(1, 8, 16384, 64, True, bf, bf) == big                         # long loop, two tiles per CU
     monkeypatch.setenv("NAUT_ATTN_VARIANT", "w4q64")
     assert nb.variant_name(1, 2, 256, 64, False, bf, bf) == "fwd_bm256_w4q64_bn64"
     monkeypatch.setenv("NAUT_ATTN_VARIANT", "nonsense")   # a name that selects nothing is reported, not ignored
