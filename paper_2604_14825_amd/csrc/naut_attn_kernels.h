@@ -29,9 +29,10 @@
 //                                      S^T accumulator registers (no shuffle: the MFMA k-slot <-> key
 //                                      assignment is chosen to match the accumulator layout)
 //
-// K and V tiles are multi-buffered in LDS, one barrier per tile: kernel 1 stages
-// them through registers (two buffers), kernel 2 and the D = 256 instantiation load
-// them straight from global memory into LDS several tiles ahead (four buffers).
+// K and V tiles are multi-buffered in LDS, one barrier per tile, and go straight from
+// global memory into LDS (global_load_lds_dwordx4, the swizzle applied to the source
+// address): one tile ahead over two buffers in kernel 1, three tiles ahead over four
+// buffers in kernel 2 and in the D = 256 instantiation.
 #ifndef NAUT_ATTN_KERNELS_H
 #define NAUT_ATTN_KERNELS_H
 #include <hip/hip_runtime.h>
@@ -120,7 +121,7 @@ struct XMfma<NAUT_F16> {
 };
 
 // ---- kernel 1: 128 queries per work-group, 4 wavefronts x 32 queries ----
-// Two work-groups per CU and 64 keys per step for D <= 128.  D = 256 doubles the O accumulator and the
+// Two work-groups per CU (four at D = 64) and 64 keys per step for D <= 128.  D = 256 doubles the O accumulator and the
 // Q fragments of a lane (192 registers between them), so it runs one work-group per CU on the full
 // 512-register budget, 32 keys per step (the four tile buffers then still fill 64 KB).
 
