@@ -482,7 +482,7 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
                 for (int r = 0; r < 16; ++r) {
                     const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, -m_new));
                     sacc[kb][r] = pv;
-                    psum += pv;
+                    psum = (kb | r) == 0 ? pv : psum + pv;
                 }
             // O^T += V^T . P^T, 16 keys per MFMA
 #pragma unroll
@@ -877,15 +877,17 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 oacc[hf][db][r] = 0.f;
-    // reference maximum (log2 units), its negation, running sum of P, running sum of P as rounded for the
-    // second product (see "the two sums" at the pieces of a stage)
-    float m_run[QH], neg_m[QH], l_run[QH], lr_run[QH];
+    // reference maximum (log2 units), its negation, a quarter of the running sum of P (kept as the quarter
+    // because that is what a block's sum is compared with: one FMA per block adds to it, and the factor is
+    // exact), and what the sum of P as rounded for the second product has over the unrounded sum (touched in
+    // heavy blocks only; see "the two sums" at the pieces of a stage)
+    float m_run[QH], neg_m[QH], lq_run[QH], dl_run[QH];
 #pragma unroll
     for (int hf = 0; hf < QH; ++hf) {
         m_run[hf] = M_INIT;
         neg_m[hf] = -M_INIT;
-        l_run[hf] = 0.f;
-        lr_run[hf] = 0.f;
+        lq_run[hf] = 0.f;
+        dl_run[hf] = 0.f;
     }
 
     // SM(kblk) part 0: causal / tail / out-of-range masking
@@ -989,7 +991,11 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 // defined the value would make the compiler pad the next use with a wait state.
                 asm volatile("" ::"v"(pe[hf][idx]));
             } else {
-                psum[hf] += pe[hf][idx];  // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
+                // fp32 sum of the unrounded P: lse needs l to better than bf16 accuracy
+                if constexpr (idx == 0)
+                    psum[hf] = pe[hf][0];
+                else
+                    psum[hf] += pe[hf][idx];
                 if constexpr (idx % 2 == 1) {
                     int w = T::pack2(pe[hf][idx - 1], pe[hf][idx]);
                     asm volatile("" ::"v"(w), "v"(psum[hf]));
@@ -1034,10 +1040,11 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf) {
             over = over || psum[hf] > T::P_LIMIT;
-            heavy = heavy || psum[hf] > 0.25f * l_run[hf];
+            heavy = heavy || psum[hf] > lq_run[hf];
         }
-        if (__builtin_amdgcn_ballot_w64(heavy || over) != 0) {
-        if (__builtin_amdgcn_ballot_w64(over) != 0) {
+        const unsigned long long over_mask = __builtin_amdgcn_ballot_w64(over);
+        if ((over_mask | __builtin_amdgcn_ballot_w64(heavy)) != 0) {  // two lane masks and a scalar OR: no vector work
+        if (over_mask != 0) {
             // Rare path: some row of this wavefront met scores far above its reference maximum.  Move
             // the reference of every row to its true running maximum, apply the repair factor
             // exp2(m_old - m_new) to l and O (after Y(k-1), whose P was formed against the old
@@ -1058,8 +1065,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 const float cand = max3(a2, b2, b2) * c;  // -inf if the block is masked for this row
                 const float m_new = max3(m_run[hf], cand, cand);
                 const float alpha = __builtin_amdgcn_exp2f(m_run[hf] - m_new);
-                l_run[hf] *= alpha;
-                lr_run[hf] *= alpha;
+                lq_run[hf] *= alpha;
+                dl_run[hf] *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -1080,7 +1087,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
                 psum[hf] = ps;
             }
         }
-        // the heavy block's sum of the rounded P; the difference to the unrounded sum goes to lr_run
+        // the heavy block's sum of the rounded P; its difference to the unrounded sum goes to dl_run
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf) {
             float pr = -psum[hf];
@@ -1089,7 +1096,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     pr = T::add_pair(p_out[hf][t][e], pr);
-            lr_run[hf] += pr;
+            dl_run[hf] += pr;
         }
         }
 #pragma unroll
@@ -1097,8 +1104,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
             for (int db = 0; db < DB; ++db)
                 pin_acc(oacc[hf][db]);
-            l_run[hf] += psum[hf];
-            lr_run[hf] += psum[hf];
+            lq_run[hf] = __builtin_fmaf(psum[hf], 0.25f, lq_run[hf]);
         }
     };
 
@@ -1270,8 +1276,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf) {
             const int q = qrow[hf];
-            const float lt = half_sum(l_run[hf]);
-            const float inv_l = 1.0f / half_sum(lr_run[hf]);  // rows beyond S: staged, never stored
+            const float lt = 4.0f * half_sum(lq_run[hf]);
+            const float inv_l = 1.0f / (lt + half_sum(dl_run[hf]));  // rows beyond S: staged, never stored
             if (p.lse != nullptr && h == 0 && q < S)
                 p.lse[(size_t)bh * S + q] = (m_run[hf] + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
 #pragma unroll
@@ -1305,8 +1311,8 @@ __global__ __launch_bounds__(NWV * 64, 1) void naut_fwd_kernel_v2(const Params p
 #pragma unroll
         for (int hf = 0; hf < QH; ++hf) {
             const int q = qrow[hf];
-            const float lt = half_sum(l_run[hf]);
-            const float lr = half_sum(lr_run[hf]);
+            const float lt = 4.0f * half_sum(lq_run[hf]);
+            const float lr = lt + half_sum(dl_run[hf]);
             if (q >= S)
                 continue;
             const float inv_l = 1.0f / lr;

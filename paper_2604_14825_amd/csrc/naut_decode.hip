@@ -323,7 +323,7 @@ __global__ __launch_bounds__(dec_waves(D) * 64, 1) void naut_decode_split_kernel
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             s_[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_[r], c, -m_run));
-            psum += s_[r];
+            psum = r == 0 ? s_[r] : psum + s_[r];
         }
         l_run += psum;
 #pragma unroll
@@ -523,7 +523,7 @@ __global__ __launch_bounds__(DEC_THREADS, 1) void naut_decode_split_fp8_kernel(c
             for (int r = 0; r < 16; ++r) {
                 const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, shift));
                 sacc[kb][r] = pv;
-                psum += pv;
+                psum = (kb | r) == 0 ? pv : psum + pv;
             }
         l_run += psum;
 #pragma unroll

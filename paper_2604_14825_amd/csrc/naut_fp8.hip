@@ -289,7 +289,7 @@ __global__ __launch_bounds__(F8_THREADS, 2) void naut_fwd_kernel_fp8(const Fp8Pa
                 for (int r = 0; r < 16; ++r) {
                     const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, shift));
                     sacc[kb][r] = pv;
-                    psum += pv;
+                    psum = (kb | r) == 0 ? pv : psum + pv;
                 }
             l_run += psum;
             // P as the B operand: k-slot 16*kb + r of this lane half is score register r of block kb
