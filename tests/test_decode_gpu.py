@@ -207,3 +207,29 @@ def test_decode_long_cache_wide_heads():
     torch.cuda.synchronize()
     o_ref, lse_ref = oracle.attn_cross16(q, k, v, synth.BF16, True, scale)
     gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode long D=256")
+
+
+@pytest.mark.parametrize("D", [64, 128, 256])
+def test_decode_cache_rows_16_mib_apart(D):
+    """K and V rows at the largest row stride the entry point admits (2^23 elements): Sk times the stride passes
+    2^32 bytes, so block addresses must be formed in 64 bits, and 31 rows of it must fit the 32-bit offsets."""
+    B, Hq, Hkv, Sq, Sk, idt = 1, 4, 1, 1, 300, synth.BF16
+    stride = 1 << 23
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, idt, 7900 + D)
+    scale = 1.0 / math.sqrt(D)
+
+    def spread(a):
+        buf = torch.empty(Sk * stride, dtype=torch.bfloat16, device="cuda")  # 4.7 GiB, rows at the start of each pitch
+        rows = buf.view(Sk, stride)[:, :D]
+        rows.copy_(gu.to_device(a, idt)[0, 0])
+        return rows.unsqueeze(0).unsqueeze(0)  # logical [1,1,Sk,D]
+    kd, vd = spread(k), spread(v)
+    assert kd.stride(2) * 2 * Sk > 1 << 32
+    od = torch.full((B, Hq, Sq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, Sk, D), dtype=torch.uint8, device="cuda")
+    print("decode, 16 MiB row stride", D, flush=True)
+    nb.naut_attn_decode_strided(gu.to_device(q, idt), kd, vd, od, lse, True, scale, ws)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, True, scale)
+    gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode D=%d, row stride 2^23" % D)

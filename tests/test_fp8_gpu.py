@@ -311,3 +311,41 @@ def test_fp8_decode_sequence_major_cache_and_narrow_heads(B, Hq, Hkv, Sq, Sk, D,
         nb.naut_attn_decode_fp8(dev(q), dev(k), dev(v), o2, None, causal, scale, DQ, DK, DV, ws)
         torch.cuda.synchronize()
         assert torch.equal(o2, od.contiguous())
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_fp8_rows_8_mib_apart(D):
+    """FP8 K and V rows at the largest row stride the entry points admit (2^23 bytes), prefill and decode: S times
+    the stride passes 2^32, so tile addresses must be formed in 64 bits, and 63 rows of it must fit 32-bit offsets."""
+    B, Hq, Hkv, S = 1, 2, 1, 600
+    stride = 1 << 23
+    q, k, v = make(B, Hq, Hkv, S, D, 12100 + D, S // 50)
+    scale = 1.0 / math.sqrt(D)
+
+    def spread(a):
+        buf = torch.empty(S * stride, dtype=torch.uint8, device="cuda")  # 4.7 GiB, rows at the start of each pitch
+        rows = buf.view(S, stride)[:, :D]
+        rows.copy_(torch.from_numpy(a).cuda()[0, 0])
+        return rows.unsqueeze(0).unsqueeze(0)  # logical [1,1,S,D]
+    kd, vd = spread(k), spread(v)
+    assert kd.stride(2) * S > 1 << 32
+    qd = torch.from_numpy(q).cuda()
+    o = torch.full((B, Hq, S, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, S), float("nan"), dtype=torch.float32, device="cuda")
+    print("fp8, 8 MiB row stride", D, flush=True)
+    nb.naut_attn_fwd_fp8_strided(qd, kd, vd, o, lse, True, scale, DQ, DK, DV)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_rows_e4m3(q, k, v, DQ, DK, DV, True, scale)
+    check(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, v, "fp8 row stride 2^23",
+          error_sigma(q, k, v, o_ref, lse_ref, True, scale))
+    # the last two positions as a decode call on the same cache
+    Sq = 2
+    qs = np.ascontiguousarray(q[:, :, S - Sq:])
+    od = torch.full((B, Hq, Sq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lsed = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.decode_workspace_bytes(B, Hq, Hkv, Sq, S, D), dtype=torch.uint8, device="cuda")
+    nb.naut_attn_decode_fp8_strided(torch.from_numpy(qs).cuda(), kd, vd, od, lsed, True, scale, DQ, DK, DV, ws)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attn_cross_e4m3(qs, k, v, DQ, DK, DV, True, scale)
+    check(od.double().cpu().numpy(), lsed.double().cpu().numpy(), o_ref, lse_ref, v, "fp8 decode row stride 2^23",
+          error_sigma(qs, k, v, o_ref, lse_ref, True, scale))

@@ -207,10 +207,14 @@ def test_wide_head_24_heads_groups_of_two():
     gu.check(o.reshape(-1, D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, "D=256, 24 heads")
 
 
-def test_wide_head_row_stride_beyond_32_bits():
-    """D = 256 with K and V rows 16 MiB apart (the largest row stride the entry point admits): S times the
-    stride passes 2^32 bytes, so the tile addresses must be formed in 64 bits."""
-    B, H, S, D, idt = 1, 1, 300, 256, synth.BF16
+@pytest.mark.parametrize("D,variant", [(256, None), (128, "bm128"), (128, "w8q32"), (128, "w4q64"), (64, "bm128")])
+def test_wide_head_row_stride_beyond_32_bits(D, variant, monkeypatch):
+    """K and V rows 16 MiB apart (the largest row stride the entry point admits), on every kernel: S times the
+    stride passes 2^32 bytes, so the tile addresses must be formed in 64 bits, and 63 rows of it must fit the
+    32-bit offsets inside a tile."""
+    if variant is not None:
+        monkeypatch.setenv("NAUT_ATTN_VARIANT", variant)
+    B, H, S, idt = 1, 1, 300, synth.BF16
     stride = 1 << 23  # elements
     q, k, v = make(B, H, H, S, D, idt, 9700)
     scale = 1.0 / math.sqrt(D)
@@ -224,7 +228,7 @@ def test_wide_head_row_stride_beyond_32_bits():
     kd, vd = spread(k), spread(v)
     assert kd.stride(2) == stride and kd.stride(2) * 2 * S > 1 << 32
     od = torch.full((B, H, S, D), float("nan"), dtype=torch.float32, device="cuda")
-    print("wide head, 16 MiB row stride", flush=True)
+    print("16 MiB row stride", D, variant, flush=True)
     o, lse = run_strided(qd, kd, vd, od, True, scale)
     o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, True, scale)
-    gu.check(o, lse, o_ref, lse_ref, "D=256, row stride 2^23")
+    gu.check(o, lse, o_ref, lse_ref, "D=%d %s, row stride 2^23" % (D, variant))
