@@ -233,3 +233,15 @@ def test_decode_cache_rows_16_mib_apart(D):
     torch.cuda.synchronize()
     o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, True, scale)
     gu.check(od.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, "decode D=%d, row stride 2^23" % D)
+
+
+@pytest.mark.parametrize("Sk,Sq", [(131072, 1), (100003, 3)])
+def test_decode_very_long_cache(Sk, Sq):
+    """Caches well beyond the benchmark's 16k positions (many splits per head, ragged last block)."""
+    B, Hq, Hkv, D, idt = 1, 8, 2, 128, synth.BF16
+    q, k, v = make(B, Hq, Hkv, Sq, Sk, D, idt, 7950 + Sq, Sk // 100)
+    scale = 1.0 / math.sqrt(D)
+    print("decode very long cache", Sk, Sq, flush=True)
+    o, lse = gu.run_hip_decode(q, k, v, idt, idt, True, scale)
+    o_ref, lse_ref = oracle.attn_cross16(q, k, v, idt, True, scale)
+    gu.check(o, lse, o_ref, lse_ref, "decode Sk=%d" % Sk)

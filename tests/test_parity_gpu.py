@@ -241,6 +241,25 @@ def test_large_workloads_sampled_rows(name, nrand):
     gu.check(o.reshape(-1, w.D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, name)
 
 
+@pytest.mark.parametrize("S,causal", [(32768, True), (65573, True), (40000, False)])
+def test_longest_sequences_sampled_rows(S, causal):
+    """The paper's longest sequence (2^15, Section 6) and beyond it, with a ragged tail: grouped-query heads,
+    outlier keys, the first and last tiles and random rows against the oracle."""
+    B, Hq, Hkv, D, idt = 1, 8, 2, 128, synth.BF16
+    q = synth.fill(B, Hq, S, D, 31000 + S, synth.TAG_Q, idt)
+    k = synth.fill(B, Hkv, S, D, 31000 + S, synth.TAG_K, idt, S // 100, 8.0)
+    v = synth.fill(B, Hkv, S, D, 31000 + S, synth.TAG_V, idt)
+    scale = 1.0 / math.sqrt(D)
+    print("long sequence", S, causal, flush=True)
+    o, lse = gu.run_hip(q, k, v, idt, idt, causal, scale)
+    assert np.isfinite(o).all() and np.isfinite(lse).all()
+    g = np.random.default_rng(S)
+    rows = np.unique(np.concatenate([np.arange(0, 260), np.arange(B * Hq * S - 260, B * Hq * S),
+                                     g.integers(0, B * Hq * S, 400)])).astype(np.int64)
+    o_ref, lse_ref = oracle.attn_rows(q, k, v, idt, causal, scale, rows=rows)
+    gu.check(o.reshape(-1, D)[rows], lse.reshape(-1)[rows], o_ref, lse_ref, "S=%d" % S)
+
+
 def test_run_to_run_bit_identical():
     w = synth.WORKLOADS["encoder"]
     q, k, v = synth.make_inputs(w)
