@@ -47,6 +47,9 @@
 #include "naut_attn.h"
 #include "naut_common.h"
 
+#ifndef NAUT_KPF
+#define NAUT_KPF 2
+#endif
 #ifndef NAUT_K1_NBUF
 #define NAUT_K1_NBUF 2
 #endif
@@ -403,9 +406,12 @@ __global__ __launch_bounds__(NTHREADS, D > 128 ? 1 : 2) void naut_fwd_kernel_bm1
             for (int kb = 0; kb < KB; ++kb) {
                 if constexpr (WIDE) {
                     // The compiler moves nothing across the asm MFMAs, so the fragment reads are put
-                    // KPF MFMAs ahead of their use by hand (one read at a time would expose the whole
-                    // LDS latency 16 times per step).
-                    constexpr int KPF = 8;
+                    // KPF MFMAs ahead of their use by hand.  Measured at S = 16384: reading each fragment
+                    // right before its MFMA exposes the LDS latency 16 times per step (714 TFLOP/s), one
+                    // ahead 829, two 850, three 846, four 843, six 839, eight 835, twelve 825, sixteen 812:
+                    // two reads in flight cover the latency, more only lengthen the wait before the first
+                    // MFMA of the step.
+                    constexpr int KPF = NAUT_KPF;
                     i32x4_t kf[KS];
 #pragma unroll
                     for (int ks = 0; ks < KPF; ++ks)
