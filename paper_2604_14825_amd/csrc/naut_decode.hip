@@ -65,7 +65,7 @@ struct DecodeParams {
     // byte strides of batch, head and sequence position (the D axis is contiguous)
     long long q_bs, q_hs, k_bs, k_hs, v_bs, v_hs, o_bs, o_hs;
     int q_rs, k_rs, v_rs, o_rs;
-    // The kernels are compiled for D = 64 or 128; a smaller head dimension runs on the next wider one:
+    // The kernels are compiled for D = 64, 128 or 256 (FP8: 64 or 128); a smaller head dimension runs on the next wider one:
     // cpr 16-byte chunks of every row are real, the chunks of Q beyond them read as zero, those of K and
     // V repeat a real chunk (they meet zeros of Q, or end in columns of O that are not stored).
     int cpr;
